@@ -1,0 +1,73 @@
+"""One peer's stage step with stale gradients (fp64).
+
+TEST INFRASTRUCTURE ONLY - see oracle/__init__.py.
+
+Follows the peer body of the paper's Alg. 1 with the update of Eq. 2:
+forward(mb) evaluates the block at the CURRENT parameters and remembers that
+parameter state; backward(mb) computes the exact gradient of the block at the
+remembered state (Eq. 2: the gradient is taken at the parameters in force
+when that batch's forward ran), applies x <- x - eta * g to this block only
+(Eq. 4: the sampling matrix keeps the peer's own block) and returns the
+gradient for the preceding peer.
+
+Plainly: a snapshot of the whole vector per in-flight microbatch, the forward
+recomputed inside backward.  At most tau+1 microbatches may be in flight.
+"""
+import numpy as np
+from . import blocks
+
+
+class StashFull(Exception):
+    pass
+
+
+class UnknownMicrobatch(Exception):
+    pass
+
+
+class DuplicateMicrobatch(Exception):
+    pass
+
+
+class Stage:
+    def __init__(self, kind, tau, eta, flat_w, *, dims=None, n_blocks=None, d=None, h=None,
+                 f=None, eps=1e-5):
+        assert kind in ("mlp", "decoder")
+        self.kind, self.tau, self.eta = kind, int(tau), float(eta)
+        self.dims, self.n_blocks, self.d, self.h, self.f, self.eps = dims, n_blocks, d, h, f, eps
+        self.w = np.array(flat_w, dtype=np.float64)  # owns a copy
+        self.k = 0                                     # number of updates applied
+        self.live = {}                                 # mb_id -> (w snapshot, input, k at forward)
+        self.last_grad = None
+        self.last_staleness = None
+
+    def _f(self, w, x):
+        if self.kind == "mlp":
+            return blocks.mlp_forward(w, self.dims, x)
+        return blocks.decoder_forward(w, self.n_blocks, self.d, self.h, self.f, self.eps, x)
+
+    def _vjp(self, w, x, dy):
+        if self.kind == "mlp":
+            return blocks.mlp_backward(w, self.dims, x, dy)
+        return blocks.decoder_backward(w, self.n_blocks, self.d, self.h, self.f, self.eps, x, dy)
+
+    def forward(self, mb_id, x):
+        if mb_id in self.live:
+            raise DuplicateMicrobatch(mb_id)
+        if len(self.live) >= self.tau + 1:
+            raise StashFull(mb_id)
+        x = np.array(x, dtype=np.float64)
+        w_mb = self.w.copy()
+        self.live[mb_id] = (w_mb, x, self.k)
+        return self._f(w_mb, x)
+
+    def backward(self, mb_id, dy):
+        if mb_id not in self.live:
+            raise UnknownMicrobatch(mb_id)
+        w_mb, x, k_fwd = self.live.pop(mb_id)
+        dx, g = self._vjp(w_mb, x, np.array(dy, dtype=np.float64))
+        self.w = self.w - self.eta * g
+        self.last_grad = g
+        self.last_staleness = self.k - k_fwd
+        self.k += 1
+        return dx
