@@ -1,0 +1,163 @@
+/*
+ * rv.h - C ABI of the stage-step / cluster-average library for one MI355X (gfx950).
+ *
+ * The calls follow the problem statement of "Ravnest: Decentralized Asynchronous
+ * Training on Heterogeneous Devices" (arXiv 2401.01728):
+ *
+ *   - a peer ("stage") owns one contiguous block x_{c,p} of the model (Eq. 1),
+ *   - it runs forward passes on arriving activations and, on arriving gradients,
+ *     a backward pass followed at once by the stale-gradient update of Eq. 2
+ *     (Alg. 1, the two branches of the peer loop),
+ *   - clusters average their parameters with a Parallel Multi-Ring All-Reduce
+ *     (section 3.2); here all C replicas live in one GPU's memory and only the
+ *     arithmetic of that reduction is performed.
+ *
+ * Conventions
+ *   - "device" pointers are HIP device memory on the current device; "host"
+ *     pointers are ordinary process memory.  The library never takes ownership
+ *     of a caller buffer.
+ *   - Every call validates its arguments on the host, enqueues its work on the
+ *     stage's (or the given) hipStream_t and returns without synchronising.
+ *     A caller buffer may be reused once the stream has passed the call.
+ *   - Errors are returned, never thrown; after a non-OK return the stage state
+ *     is unchanged.
+ *
+ * Canonical flat parameter order (what set/get_params, last_grad and the
+ * average see), layers in forward order, every matrix row-major [in, out]:
+ *   MLP stage      : W_0, b_0, W_1, b_1, ...
+ *   decoder block  : ln1.gamma[d], ln1.beta[d], Wqkv[d,3d] (column thirds q|k|v,
+ *                    heads contiguous inside a third), bqkv[3d], Wo[d,d], bo[d],
+ *                    ln2.gamma[d], ln2.beta[d], W1[d,f], b1[f], W2[f,d], b2[d]
+ */
+#ifndef RV_H
+#define RV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rv_stage rv_stage; /* opaque, library-owned */
+
+typedef enum {
+  RV_OK = 0,
+  RV_E_INVAL = -1,      /* bad argument (null pointer, non-positive size, d % heads != 0, ...) */
+  RV_E_STASH_FULL = -2, /* forward with tau+1 microbatches already in flight            */
+  RV_E_UNKNOWN_MB = -3, /* backward of a microbatch id that is not in flight             */
+  RV_E_DUP_MB = -4,     /* forward of a microbatch id that is already in flight          */
+  RV_E_NOMEM = -5,      /* device or host allocation failed                              */
+  RV_E_DEVICE = -6      /* a HIP call failed                                             */
+} rv_status;
+
+typedef enum { RV_MLP = 0, RV_DECODER = 1 } rv_kind;
+typedef enum { RV_F32 = 0, RV_BF16 = 1 } rv_dtype;
+
+/*
+ * Description of one stage.
+ *   kind RV_MLP     : n_layers Linear layers with ReLU between them (none after
+ *                     the last); dims = n_layers+1 widths; dtype must be RV_F32;
+ *                     activations are fp32 [microbatch, width].
+ *   kind RV_DECODER : n_layers pre-LayerNorm decoder blocks (causal self
+ *                     attention, GELU feed-forward); dims = {d_model, n_heads,
+ *                     d_ffn, seq}; dtype must be RV_BF16: activations and
+ *                     gradients at the boundary are bf16 [microbatch, seq, d_model],
+ *                     matrix products take bf16 operands with fp32 accumulation,
+ *                     the master parameters are fp32.  d_model / n_heads must be
+ *                     64 or 128; d_model, d_ffn multiples of 64; seq a multiple of 64.
+ *   tau             : largest number of updates that may happen between a
+ *                     microbatch's forward and its backward (the staleness bound
+ *                     of Eq. 2); the stage keeps tau+1 activation-stash slots and
+ *                     tau+1 weight versions.
+ *   eta             : learning rate of Eq. 2.
+ *   stream          : hipStream_t (borrowed); NULL = the default stream.
+ */
+typedef struct {
+  int32_t kind;
+  int32_t dtype;
+  int32_t n_layers;
+  const int64_t* dims; /* host */
+  int32_t microbatch;
+  int32_t tau;
+  float eta;
+  float ln_eps;
+  void* stream;
+} rv_stage_desc;
+
+/* Allocates master parameters (zero), gradient buffer, tau+1 weight versions and
+ * tau+1 stash slots on the current device.  RV_E_INVAL / RV_E_NOMEM / RV_E_DEVICE. */
+rv_status rv_stage_create(const rv_stage_desc* desc, rv_stage** out);
+rv_status rv_stage_destroy(rv_stage* s);
+
+/* Length P of the flat parameter vector (0 for a NULL stage). */
+size_t rv_stage_num_params(const rv_stage* s);
+
+/* Number of microbatches forwarded and not yet backwarded. */
+int rv_stage_in_flight(const rv_stage* s);
+
+/* Replace the fp32 master vector (device [n], n == P) and make it the current
+ * weight version.  Only legal with no microbatch in flight (RV_E_INVAL otherwise). */
+rv_status rv_stage_set_params(rv_stage* s, const float* flat, size_t n);
+/* Copy the fp32 master vector into flat_out (device [n], n == P). */
+rv_status rv_stage_get_params(const rv_stage* s, float* flat_out, size_t n);
+/* Copy the parameter gradient computed by the most recent backward (device [n]). */
+rv_status rv_stage_last_grad(const rv_stage* s, float* flat_out, size_t n);
+
+/*
+ * Forward branch of Alg. 1: out = forward_pass(x_{c,p}, in) at the CURRENT
+ * parameters.  Binds mb_id to a stash slot and to the current weight version.
+ * in/out: device, MLP fp32 [microbatch, dims[0]] -> [microbatch, dims[n_layers]];
+ * decoder bf16 [microbatch, seq, d_model] -> same shape.
+ * RV_E_STASH_FULL when tau+1 microbatches are in flight; RV_E_DUP_MB.
+ */
+rv_status rv_stage_forward(rv_stage* s, int64_t mb_id, const void* in, void* out);
+
+/*
+ * Backward branch of Alg. 1 with the update of Eq. 2: computes the exact
+ * gradient of the block at the weights and activations of mb_id's forward
+ * (the stale gradient g^{k - tau_k}), writes the gradient for the preceding
+ * peer to grad_in (may be NULL), applies x <- x - eta * g to this stage's
+ * block only (Eq. 4) and publishes the result as the newest weight version.
+ * Any in-flight id is legal.  RV_E_UNKNOWN_MB.
+ */
+rv_status rv_stage_backward(rv_stage* s, int64_t mb_id, const void* grad_out, void* grad_in);
+
+/*
+ * The update of Eq. 2 on a bare vector: w[i] <- w[i] - eta * g[i] (one fused
+ * multiply-add in fp32), optionally also emitting the bf16 rounding of the new
+ * w into bf16_out (device [n] of 16-bit words, may be NULL).  All device.
+ */
+rv_status rv_block_update(float* w, const float* g, size_t n, float eta, void* bf16_out,
+                          void* stream);
+
+/*
+ * Arithmetic of one cycle of Parallel Multi-Ring All-Reduce (section 3.2) over C
+ * replicas of an n-vector that all reside on this GPU.
+ *   replicas     host array of C device pointers, each fp32 [n]; must not alias
+ *                one another or mean_out.  1 <= C <= 64.
+ *   R            number of rings, 1 <= R <= 4096.  Ring r owns elements
+ *                [floor(r n / R), floor((r+1) n / R)); inside it chunk j owns
+ *                [lo + floor(j S / C), lo + floor((j+1) S / C)), S the segment size.
+ *                Chunk j is summed in ring order x_j + x_{j+1} + ... + x_{j-1}
+ *                (indices mod C, fp32, left to right) and divided by C once.
+ *   mean_out     device [n] or NULL (NULL only with write_back).
+ *   write_back   nonzero: every replica is overwritten with the mean, the state
+ *                the paper's cycle ends in.
+ *   grad,grad_replica,eta   if grad != NULL (device [n]) replica grad_replica
+ *                enters the average as x - eta*grad (Alg. 2, the all-reduce
+ *                branch), so the mean moves by -(eta/C) grad (Eq. 17).  The
+ *                product and the subtraction are rounded separately.
+ * RV_E_INVAL on bad arguments.  Pointers that are not 16-byte aligned are
+ * accepted (slower path).
+ */
+rv_status rv_cluster_average(float* const* replicas, int C, size_t n, int R, float* mean_out,
+                             int write_back, const float* grad, int grad_replica, float eta,
+                             void* stream);
+
+const char* rv_strerror(rv_status st);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RV_H */

@@ -1,0 +1,70 @@
+"""Loads librv.so (and librvgen.so) with ctypes.  No fallbacks: a missing library is an error."""
+import ctypes
+import os
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "librv.so")
+GEN_PATH = os.path.join(HERE, "inputs", "librvgen.so")
+
+c_void_p, c_int, c_int32, c_int64, c_size_t, c_float, c_uint32, c_uint64 = (
+    ctypes.c_void_p, ctypes.c_int, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t,
+    ctypes.c_float, ctypes.c_uint32, ctypes.c_uint64)
+
+
+class StageDesc(ctypes.Structure):
+    _fields_ = [("kind", c_int32), ("dtype", c_int32), ("n_layers", c_int32),
+                ("dims", ctypes.POINTER(c_int64)), ("microbatch", c_int32), ("tau", c_int32),
+                ("eta", c_float), ("ln_eps", c_float), ("stream", c_void_p)]
+
+
+# every symbol include/rv.h declares: name -> (restype, argtypes)
+SYMBOLS = {
+    "rv_stage_create": (c_int, [ctypes.POINTER(StageDesc), ctypes.POINTER(c_void_p)]),
+    "rv_stage_destroy": (c_int, [c_void_p]),
+    "rv_stage_num_params": (c_size_t, [c_void_p]),
+    "rv_stage_in_flight": (c_int, [c_void_p]),
+    "rv_stage_set_params": (c_int, [c_void_p, c_void_p, c_size_t]),
+    "rv_stage_get_params": (c_int, [c_void_p, c_void_p, c_size_t]),
+    "rv_stage_last_grad": (c_int, [c_void_p, c_void_p, c_size_t]),
+    "rv_stage_forward": (c_int, [c_void_p, c_int64, c_void_p, c_void_p]),
+    "rv_stage_backward": (c_int, [c_void_p, c_int64, c_void_p, c_void_p]),
+    "rv_block_update": (c_int, [c_void_p, c_void_p, c_size_t, c_float, c_void_p, c_void_p]),
+    "rv_cluster_average": (c_int, [ctypes.POINTER(c_void_p), c_int, c_size_t, c_int, c_void_p, c_int,
+                                   c_void_p, c_int, c_float, c_void_p]),
+    "rv_strerror": (ctypes.c_char_p, [c_int]),
+}
+
+GEN_SYMBOLS = {
+    "rvgen_fill_normal": (c_int, [c_void_p, c_uint64, c_uint32, c_uint32, c_float, c_float, c_uint64,
+                                  c_float, c_int, c_void_p]),
+    "rvgen_fill_uniform": (c_int, [c_void_p, c_uint64, c_uint32, c_uint32, c_float, c_float, c_uint64,
+                                   c_void_p]),
+}
+
+_lib = None
+_gen = None
+
+
+def _load(path, table):
+    if not os.path.exists(path):
+        raise RuntimeError(
+            "%s is not built; run `python -m paper_2401_01728_amd.build` (there is no fallback path)" % path)
+    lib = ctypes.CDLL(path)
+    for name, (res, args) in table.items():
+        fn = getattr(lib, name)          # AttributeError if the symbol is missing
+        fn.restype, fn.argtypes = res, args
+    return lib
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = _load(LIB_PATH, SYMBOLS)
+    return _lib
+
+
+def genlib():
+    global _gen
+    if _gen is None:
+        _gen = _load(GEN_PATH, GEN_SYMBOLS)
+    return _gen

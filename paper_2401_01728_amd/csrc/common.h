@@ -1,0 +1,35 @@
+// Internal helpers shared by the library's translation units (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/rv.h"
+
+#define RV_HIP_TRY(expr)                         \
+  do {                                           \
+    hipError_t _e = (expr);                      \
+    if (_e != hipSuccess) return RV_E_DEVICE;    \
+  } while (0)
+
+#define RV_TRY(expr)                 \
+  do {                               \
+    rv_status _s = (expr);           \
+    if (_s != RV_OK) return _s;      \
+  } while (0)
+
+static inline rv_status rv_launch_status() {
+  return hipGetLastError() == hipSuccess ? RV_OK : RV_E_DEVICE;
+}
+
+// fp32 -> bf16 bits, round to nearest even (finite inputs).
+__device__ __forceinline__ uint16_t rv_f32_to_bf16(float x) {
+  uint32_t b = __float_as_uint(x);
+  b += 0x7FFFu + ((b >> 16) & 1u);
+  return (uint16_t)(b >> 16);
+}
+__device__ __forceinline__ float rv_bf16_to_f32(uint16_t h) {
+  return __uint_as_float(((uint32_t)h) << 16);
+}
+__device__ __forceinline__ uint32_t rv_pack_bf16x2(float lo, float hi) {
+  return (uint32_t)rv_f32_to_bf16(lo) | ((uint32_t)rv_f32_to_bf16(hi) << 16);
+}

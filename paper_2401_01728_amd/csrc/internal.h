@@ -1,0 +1,50 @@
+// Internal interfaces between the library's translation units (not part of the ABI).
+#pragma once
+#include <vector>
+#include "common.h"
+
+// ---- update.hip ------------------------------------------------------------------
+// copy_kind: 0 none, 1 bf16 bits, 2 fp32
+rv_status rv_launch_update(float* w, const float* g, size_t n, float eta, void* copy, int copy_kind,
+                           hipStream_t st);
+rv_status rv_launch_publish(const float* w, size_t n, void* copy, int copy_kind, hipStream_t st);
+
+// ---- stage bookkeeping -------------------------------------------------------------
+struct rv_slot {
+  bool live = false;
+  int64_t mb = 0;
+  int ver = -1;          // weight-version slot bound at forward time
+  char* base = nullptr;  // activation stash of this microbatch
+};
+
+struct rv_stage {
+  int kind = 0, dtype = 0, n_layers = 0, microbatch = 0, tau = 0;
+  float eta = 0.f, ln_eps = 1e-5f;
+  std::vector<int64_t> dims;
+  hipStream_t st = nullptr;
+  size_t P = 0;
+  float* master = nullptr;  // [P] fp32
+  float* grad = nullptr;    // [P] fp32, gradient of the last backward
+  size_t ver_elem = 0;      // bytes per parameter in a version slot (2 or 4)
+  std::vector<char*> ver;   // tau+1 version slots
+  std::vector<int> ver_ref; // in-flight microbatches bound to each slot
+  int cur = 0;              // slot holding the newest version
+  std::vector<rv_slot> slots;
+  size_t slot_bytes = 0;
+  char* stash = nullptr;    // (tau+1) * slot_bytes
+  char* work = nullptr;     // scratch shared by all calls of this stage
+  size_t work_bytes = 0;
+  void* impl = nullptr;     // kind-specific plan (offsets, shapes)
+};
+
+// ---- mlp.hip -----------------------------------------------------------------------
+rv_status rv_mlp_plan(rv_stage* s);   // fills P, slot_bytes, work_bytes, impl
+void rv_mlp_free(rv_stage* s);
+rv_status rv_mlp_forward(rv_stage* s, rv_slot& slot, const void* in, void* out);
+rv_status rv_mlp_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void* grad_in);
+
+// ---- decoder.hip -------------------------------------------------------------------
+rv_status rv_dec_plan(rv_stage* s);
+void rv_dec_free(rv_stage* s);
+rv_status rv_dec_forward(rv_stage* s, rv_slot& slot, const void* in, void* out);
+rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void* grad_in);

@@ -1,0 +1,164 @@
+// Stage object: one peer of the paper's Alg. 1.  Host-side bookkeeping only:
+//   - the microbatch -> stash-slot map (at most tau+1 in flight: the paper's rule that a
+//     sender waits until the receiver's buffer has room becomes RV_E_STASH_FULL),
+//   - the ring of tau+1 weight versions.  A forward binds the microbatch to the newest
+//     version; its backward reads exactly that version (Eq. 2 takes the gradient at the
+//     parameters in force during the forward); the update that follows publishes a new
+//     version into a slot no in-flight microbatch refers to.
+// All device work is enqueued on the stage's stream by mlp.hip / decoder.hip / update.hip.
+#include <new>
+#include "internal.h"
+
+namespace {
+
+int find_slot(const rv_stage* s, int64_t mb) {
+  for (size_t i = 0; i < s->slots.size(); ++i)
+    if (s->slots[i].live && s->slots[i].mb == mb) return (int)i;
+  return -1;
+}
+
+int copy_kind(const rv_stage* s) { return s->dtype == RV_BF16 ? 1 : 2; }
+
+void free_all(rv_stage* s) {
+  if (!s) return;
+  if (s->kind == RV_MLP) rv_mlp_free(s); else rv_dec_free(s);
+  if (s->master) (void)hipFree(s->master);
+  if (s->grad) (void)hipFree(s->grad);
+  for (char* v : s->ver) if (v) (void)hipFree(v);
+  if (s->stash) (void)hipFree(s->stash);
+  if (s->work) (void)hipFree(s->work);
+  delete s;
+}
+
+}  // namespace
+
+extern "C" rv_status rv_stage_create(const rv_stage_desc* d, rv_stage** out) {
+  if (!d || !out) return RV_E_INVAL;
+  *out = nullptr;
+  if (d->kind != RV_MLP && d->kind != RV_DECODER) return RV_E_INVAL;
+  if (d->n_layers < 1 || d->n_layers > 1024 || !d->dims || d->microbatch < 1 || d->tau < 0 ||
+      d->tau > 1024)
+    return RV_E_INVAL;
+  if (!(d->eta == d->eta)) return RV_E_INVAL;
+  if (d->kind == RV_MLP && d->dtype != RV_F32) return RV_E_INVAL;
+  if (d->kind == RV_DECODER && d->dtype != RV_BF16) return RV_E_INVAL;
+  rv_stage* s = new (std::nothrow) rv_stage();
+  if (!s) return RV_E_NOMEM;
+  s->kind = d->kind; s->dtype = d->dtype; s->n_layers = d->n_layers;
+  s->microbatch = d->microbatch; s->tau = d->tau; s->eta = d->eta;
+  s->ln_eps = d->ln_eps > 0.f ? d->ln_eps : 1e-5f;
+  s->st = (hipStream_t)d->stream;
+  int nd = d->kind == RV_MLP ? d->n_layers + 1 : 4;
+  s->dims.assign(d->dims, d->dims + nd);
+  rv_status rc = d->kind == RV_MLP ? rv_mlp_plan(s) : rv_dec_plan(s);
+  if (rc != RV_OK) { free_all(s); return rc; }
+  s->ver_elem = s->dtype == RV_BF16 ? 2 : 4;
+  const int ns = s->tau + 1;
+  s->ver.assign(ns, nullptr);
+  s->ver_ref.assign(ns, 0);
+  s->slots.assign(ns, rv_slot());
+  bool ok = hipMalloc((void**)&s->master, s->P * 4) == hipSuccess &&
+            hipMalloc((void**)&s->grad, s->P * 4) == hipSuccess;
+  for (int i = 0; ok && i < ns; ++i) ok = hipMalloc((void**)&s->ver[i], s->P * s->ver_elem) == hipSuccess;
+  if (ok && s->slot_bytes) ok = hipMalloc((void**)&s->stash, s->slot_bytes * ns) == hipSuccess;
+  if (ok && s->work_bytes) ok = hipMalloc((void**)&s->work, s->work_bytes) == hipSuccess;
+  if (!ok) { (void)hipGetLastError(); free_all(s); return RV_E_NOMEM; }
+  for (int i = 0; i < ns; ++i) s->slots[i].base = s->stash + (size_t)i * s->slot_bytes;
+  if (hipMemsetAsync(s->master, 0, s->P * 4, s->st) != hipSuccess ||
+      hipMemsetAsync(s->grad, 0, s->P * 4, s->st) != hipSuccess ||
+      hipMemsetAsync(s->ver[0], 0, s->P * s->ver_elem, s->st) != hipSuccess) {
+    free_all(s); return RV_E_DEVICE;
+  }
+  s->cur = 0;
+  *out = s;
+  return RV_OK;
+}
+
+extern "C" rv_status rv_stage_destroy(rv_stage* s) {
+  if (!s) return RV_E_INVAL;
+  (void)hipStreamSynchronize(s->st);
+  free_all(s);
+  return RV_OK;
+}
+
+extern "C" size_t rv_stage_num_params(const rv_stage* s) { return s ? s->P : 0; }
+
+extern "C" int rv_stage_in_flight(const rv_stage* s) {
+  if (!s) return 0;
+  int n = 0;
+  for (const rv_slot& sl : s->slots) n += sl.live ? 1 : 0;
+  return n;
+}
+
+extern "C" rv_status rv_stage_set_params(rv_stage* s, const float* flat, size_t n) {
+  if (!s || !flat || n != s->P) return RV_E_INVAL;
+  if (rv_stage_in_flight(s) != 0) return RV_E_INVAL;
+  RV_HIP_TRY(hipMemcpyAsync(s->master, flat, n * 4, hipMemcpyDeviceToDevice, s->st));
+  return rv_launch_publish(s->master, s->P, s->ver[s->cur], copy_kind(s), s->st);
+}
+
+extern "C" rv_status rv_stage_get_params(const rv_stage* s, float* flat_out, size_t n) {
+  if (!s || !flat_out || n != s->P) return RV_E_INVAL;
+  RV_HIP_TRY(hipMemcpyAsync(flat_out, s->master, n * 4, hipMemcpyDeviceToDevice, s->st));
+  return RV_OK;
+}
+
+extern "C" rv_status rv_stage_last_grad(const rv_stage* s, float* flat_out, size_t n) {
+  if (!s || !flat_out || n != s->P) return RV_E_INVAL;
+  RV_HIP_TRY(hipMemcpyAsync(flat_out, s->grad, n * 4, hipMemcpyDeviceToDevice, s->st));
+  return RV_OK;
+}
+
+extern "C" rv_status rv_stage_forward(rv_stage* s, int64_t mb_id, const void* in, void* out) {
+  if (!s || !in || !out) return RV_E_INVAL;
+  if (find_slot(s, mb_id) >= 0) return RV_E_DUP_MB;
+  int free_i = -1;
+  for (size_t i = 0; i < s->slots.size(); ++i)
+    if (!s->slots[i].live) { free_i = (int)i; break; }
+  if (free_i < 0) return RV_E_STASH_FULL;
+  rv_slot& sl = s->slots[free_i];
+  sl.ver = s->cur;
+  rv_status rc = s->kind == RV_MLP ? rv_mlp_forward(s, sl, in, out) : rv_dec_forward(s, sl, in, out);
+  if (rc != RV_OK) { sl.ver = -1; return rc; }
+  sl.live = true; sl.mb = mb_id;
+  s->ver_ref[s->cur] += 1;
+  return RV_OK;
+}
+
+extern "C" rv_status rv_stage_backward(rv_stage* s, int64_t mb_id, const void* grad_out, void* grad_in) {
+  if (!s || !grad_out) return RV_E_INVAL;
+  int i = find_slot(s, mb_id);
+  if (i < 0) return RV_E_UNKNOWN_MB;
+  rv_slot& sl = s->slots[i];
+  rv_status rc = s->kind == RV_MLP ? rv_mlp_backward(s, sl, grad_out, grad_in)
+                                   : rv_dec_backward(s, sl, grad_out, grad_in);
+  if (rc != RV_OK) return rc;
+  // retire the microbatch, then publish the updated block as a new version in a slot that
+  // no in-flight microbatch is bound to (with tau+1 slots and at most tau left in flight
+  // there is always one; the current slot itself if nobody refers to it).
+  sl.live = false;
+  s->ver_ref[sl.ver] -= 1;
+  sl.ver = -1;
+  int dst = -1;
+  if (s->ver_ref[s->cur] == 0) dst = s->cur;
+  for (size_t v = 0; dst < 0 && v < s->ver.size(); ++v)
+    if (s->ver_ref[v] == 0) dst = (int)v;
+  if (dst < 0) return RV_E_DEVICE;  // unreachable by the counting argument above
+  rc = rv_launch_update(s->master, s->grad, s->P, s->eta, s->ver[dst], copy_kind(s), s->st);
+  if (rc != RV_OK) return rc;
+  s->cur = dst;
+  return RV_OK;
+}
+
+extern "C" const char* rv_strerror(rv_status st) {
+  switch (st) {
+    case RV_OK: return "ok";
+    case RV_E_INVAL: return "invalid argument";
+    case RV_E_STASH_FULL: return "tau+1 microbatches already in flight";
+    case RV_E_UNKNOWN_MB: return "microbatch id not in flight";
+    case RV_E_DUP_MB: return "microbatch id already in flight";
+    case RV_E_NOMEM: return "out of memory";
+    case RV_E_DEVICE: return "HIP call failed";
+  }
+  return "unknown status";
+}

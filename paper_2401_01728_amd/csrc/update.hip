@@ -1,0 +1,107 @@
+// Delayed block SGD update (paper Eq. 2; Eq. 4 restricts it to the peer's own block):
+// w <- w - eta * g on the flat fp32 master vector, one fused multiply-add per element,
+// optionally emitting the new weights as the next weight version (bf16 for the
+// decoder's matrix products, fp32 for the MLP stage).
+//
+// HBM-bound streaming kernel: reads w and g (4+4 B), writes w (4 B) and the version
+// copy (2 or 4 B) per parameter.  16-byte accesses, two vectors in flight per lane.
+#include "common.h"
+#include "internal.h"
+
+namespace {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u2 __attribute__((ext_vector_type(2)));
+
+constexpr int kThreads = 256;
+constexpr int kVec = 2;
+constexpr int kTile = kThreads * kVec * 4;
+
+// COPY: 0 none, 1 bf16, 2 fp32
+template <int COPY>
+__global__ __launch_bounds__(kThreads) void update_kernel(float* __restrict__ w,
+                                                          const float* __restrict__ g, uint64_t n,
+                                                          float eta, void* __restrict__ copy,
+                                                          int aligned) {
+  const uint64_t base = (uint64_t)blockIdx.x * kTile;
+  if (aligned && base + kTile <= n) {
+    f4 wv[kVec], gv[kVec];
+#pragma unroll
+    for (int u = 0; u < kVec; ++u) {
+      uint64_t e = base + (uint64_t)(u * kThreads + threadIdx.x) * 4;
+      wv[u] = *reinterpret_cast<const f4*>(w + e);
+      gv[u] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(g + e));
+    }
+#pragma unroll
+    for (int u = 0; u < kVec; ++u) {
+      uint64_t e = base + (uint64_t)(u * kThreads + threadIdx.x) * 4;
+      f4 r;
+      r.x = __fmaf_rn(-eta, gv[u].x, wv[u].x);
+      r.y = __fmaf_rn(-eta, gv[u].y, wv[u].y);
+      r.z = __fmaf_rn(-eta, gv[u].z, wv[u].z);
+      r.w = __fmaf_rn(-eta, gv[u].w, wv[u].w);
+      *reinterpret_cast<f4*>(w + e) = r;
+      if (COPY == 1) {
+        u2 pk;
+        pk.x = rv_pack_bf16x2(r.x, r.y);
+        pk.y = rv_pack_bf16x2(r.z, r.w);
+        *reinterpret_cast<u2*>(reinterpret_cast<uint16_t*>(copy) + e) = pk;
+      } else if (COPY == 2) {
+        *reinterpret_cast<f4*>(reinterpret_cast<float*>(copy) + e) = r;
+      }
+    }
+    return;
+  }
+  for (int k = threadIdx.x; k < kTile; k += kThreads) {
+    uint64_t i = base + k;
+    if (i >= n) break;
+    float r = __fmaf_rn(-eta, g[i], w[i]);
+    w[i] = r;
+    if (COPY == 1) reinterpret_cast<uint16_t*>(copy)[i] = rv_f32_to_bf16(r);
+    if (COPY == 2) reinterpret_cast<float*>(copy)[i] = r;
+  }
+}
+
+// plain conversion of the master vector into a version slot (set_params)
+template <int COPY>
+__global__ __launch_bounds__(kThreads) void publish_kernel(const float* __restrict__ w, uint64_t n,
+                                                           void* __restrict__ copy) {
+  uint64_t i = (uint64_t)blockIdx.x * kThreads + threadIdx.x;
+  if (i >= n) return;
+  if (COPY == 1) reinterpret_cast<uint16_t*>(copy)[i] = rv_f32_to_bf16(w[i]);
+  if (COPY == 2) reinterpret_cast<float*>(copy)[i] = w[i];
+}
+
+}  // namespace
+
+rv_status rv_launch_update(float* w, const float* g, size_t n, float eta, void* copy, int copy_kind,
+                           hipStream_t st) {
+  if (n == 0) return RV_OK;
+  int aligned = ((((uintptr_t)w) | ((uintptr_t)g)) & 15) == 0;
+  if (copy && (((uintptr_t)copy) & 15)) aligned = 0;
+  unsigned blocks = (unsigned)((n + kTile - 1) / kTile);
+  if (!copy || copy_kind == 0)
+    hipLaunchKernelGGL(update_kernel<0>, dim3(blocks), dim3(kThreads), 0, st, w, g, n, eta, nullptr, aligned);
+  else if (copy_kind == 1)
+    hipLaunchKernelGGL(update_kernel<1>, dim3(blocks), dim3(kThreads), 0, st, w, g, n, eta, copy, aligned);
+  else
+    hipLaunchKernelGGL(update_kernel<2>, dim3(blocks), dim3(kThreads), 0, st, w, g, n, eta, copy, aligned);
+  return rv_launch_status();
+}
+
+rv_status rv_launch_publish(const float* w, size_t n, void* copy, int copy_kind, hipStream_t st) {
+  if (n == 0) return RV_OK;
+  unsigned blocks = (unsigned)((n + kThreads - 1) / kThreads);
+  if (copy_kind == 1)
+    hipLaunchKernelGGL(publish_kernel<1>, dim3(blocks), dim3(kThreads), 0, st, w, n, copy);
+  else
+    hipLaunchKernelGGL(publish_kernel<2>, dim3(blocks), dim3(kThreads), 0, st, w, n, copy);
+  return rv_launch_status();
+}
+
+extern "C" rv_status rv_block_update(float* w, const float* g, size_t n, float eta, void* bf16_out,
+                                     void* stream) {
+  if (w == nullptr || g == nullptr || n == 0) return RV_E_INVAL;
+  if ((const float*)w == g) return RV_E_INVAL;
+  return rv_launch_update(w, g, n, eta, bf16_out, bf16_out ? 1 : 0, (hipStream_t)stream);
+}

@@ -1,0 +1,134 @@
+"""fp32 MLP stage vs the oracle: the tiny 2-stage chain (tau = 1 then tau = 0), MSE in the
+harness; stash / version / delayed-update semantics of paper Alg. 1 + Eq. 2 end to end.
+
+Bar (fp32 products, K <= 128): normwise 1e-5 per tensor; the update itself 1e-6 against
+w_old - eta * g_gpu in fp64.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import blocks, stage as ostage
+from paper_2401_01728_amd.inputs import gen
+from util import dev, host64, rel_l2
+
+pytestmark = pytest.mark.gpu
+
+
+def kaiming_uniform_flat(seed, dims):
+    """W ~ U(+-sqrt(6/fan_in)), b ~ U(+-1/sqrt(fan_in)), canonical flat order."""
+    parts = []
+    for i in range(len(dims) - 1):
+        fan_in = dims[i]
+        bw = np.sqrt(6.0 / fan_in); bb = 1.0 / np.sqrt(fan_in)
+        parts.append(gen.uniform_f32(seed, 2 * i, dims[i] * dims[i + 1], -bw, bw))
+        parts.append(gen.uniform_f32(seed, 2 * i + 1, dims[i + 1], -bb, bb))
+    return np.concatenate(parts).astype(np.float32)
+
+
+def test_two_stage_chain_config1():
+    import paper_2401_01728_amd as rv
+    dims, mb, n_mb, eta = [64, 128, 64], 8, 16, 0.01
+    taus = [1, 0]                      # staleness falls to zero at the last peer
+    w0 = [kaiming_uniform_flat(1 + s, dims) for s in range(2)]
+    g_st = [rv.Stage.mlp(dims, mb, taus[s], eta) for s in range(2)]
+    o_st = [ostage.Stage("mlp", taus[s], eta, w0[s], dims=dims) for s in range(2)]
+    for s in range(2):
+        assert g_st[s].num_params == 16576
+        g_st[s].set_params(dev(w0[s]))
+    xs = [gen.normal_f32(1, 100 + t, mb * 64).reshape(mb, 64) for t in range(n_mb)]
+    ts = [gen.normal_f32(1, 200 + t, mb * 64).reshape(mb, 64) for t in range(n_mb)]
+    # pipeline order: stage 0 forwards mb t, stage 1 forwards + backwards it at once (tau=0),
+    # its input gradient reaches stage 0 one step later (tau=1).
+    pending = {}
+    worst = 0.0
+    for t in range(n_mb + 1):
+        if t < n_mb:
+            h_g = g_st[0].forward(t, dev(xs[t])); h_o = o_st[0].forward(t, xs[t])
+            assert rel_l2(host64(h_g), h_o) < 1e-5
+            y_g = g_st[1].forward(t, h_g); y_o = o_st[1].forward(t, h_o)
+            assert rel_l2(host64(y_g), y_o) < 1e-5
+            dy_g = (2.0 / y_g.numel()) * (y_g - dev(ts[t]))          # harness: MSE gradient
+            dy_o = 2.0 * (y_o - ts[t]) / y_o.size
+            w_old = host64(g_st[1].get_params())
+            dh_g = g_st[1].backward(t, dy_g.contiguous()); dh_o = o_st[1].backward(t, dy_o)
+            assert rel_l2(host64(dh_g), dh_o) < 2e-5
+            gg = host64(g_st[1].last_grad())
+            assert rel_l2(gg, o_st[1].last_grad) < 2e-5
+            w_new = host64(g_st[1].get_params())
+            assert np.all(np.abs(w_new - (w_old - np.float64(np.float32(eta)) * gg)) <= 1e-6 * np.maximum(np.abs(w_old), 1e-30))
+            pending[t] = (dh_g, dh_o)
+        j = t - 1
+        if j >= 0:
+            dh_g, dh_o = pending.pop(j)
+            dx_g = g_st[0].backward(j, dh_g); dx_o = o_st[0].backward(j, dh_o)
+            assert o_st[0].last_staleness == min(j, 1)
+            assert rel_l2(host64(dx_g), dx_o) < 5e-5
+            assert rel_l2(host64(g_st[0].last_grad()), o_st[0].last_grad) < 5e-5
+    for s in range(2):
+        assert rel_l2(host64(g_st[s].get_params()), o_st[s].w) < 1e-6
+        assert g_st[s].in_flight == 0
+
+
+@pytest.mark.parametrize("dims,mb,tau", [([5, 7, 3], 3, 2), ([33, 17, 65, 9], 19, 3), ([4, 4], 1, 0)])
+def test_general_shapes_and_fifo_schedule(dims, mb, tau):
+    import paper_2401_01728_amd as rv
+    eta = 0.05
+    w0 = kaiming_uniform_flat(5, dims)
+    g = rv.Stage.mlp(dims, mb, tau, eta); g.set_params(dev(w0))
+    o = ostage.Stage("mlp", tau, eta, w0, dims=dims)
+    n = 7
+    xs = [gen.normal_f32(5, 10 + t, mb * dims[0]).reshape(mb, dims[0]) for t in range(n)]
+    dys = [gen.normal_f32(5, 50 + t, mb * dims[-1]).reshape(mb, dims[-1]) for t in range(n)]
+    for t in range(n + tau):
+        if t < n:
+            assert rel_l2(host64(g.forward(t, dev(xs[t]))), o.forward(t, xs[t])) < 1e-5
+            assert g.in_flight == len(o.live)
+        j = t - tau
+        if j >= 0:
+            dx = g.backward(j, dev(dys[j])); dxo = o.backward(j, dys[j])
+            assert rel_l2(host64(dx), dxo) < 1e-5
+            assert rel_l2(host64(g.last_grad()), o.last_grad) < 1e-5
+    assert rel_l2(host64(g.get_params()), o.w) < 1e-6
+
+
+def test_out_of_order_backward_keeps_versions_apart():
+    """Any in-flight id may be backwarded; each must see the weights of ITS forward."""
+    import paper_2401_01728_amd as rv
+    dims, mb, tau, eta = [6, 9, 4], 4, 2, 0.1
+    w0 = kaiming_uniform_flat(6, dims)
+    g = rv.Stage.mlp(dims, mb, tau, eta); g.set_params(dev(w0))
+    o = ostage.Stage("mlp", tau, eta, w0, dims=dims)
+    x = lambda t: gen.normal_f32(6, 10 + t, mb * 6).reshape(mb, 6)
+    dy = lambda t: gen.normal_f32(6, 50 + t, mb * 4).reshape(mb, 4)
+    order = [("f", 0), ("f", 1), ("b", 1), ("f", 2), ("b", 2), ("f", 3), ("b", 3), ("f", 4), ("b", 0), ("b", 4)]
+    for op, t in order:
+        if op == "f":
+            assert rel_l2(host64(g.forward(t, dev(x(t)))), o.forward(t, x(t))) < 1e-5
+        else:
+            assert rel_l2(host64(g.backward(t, dev(dy(t)))), o.backward(t, dy(t))) < 1e-5
+            assert rel_l2(host64(g.last_grad()), o.last_grad) < 1e-5
+    assert rel_l2(host64(g.get_params()), o.w) < 1e-6
+
+
+def test_error_paths_leave_state_unchanged():
+    import paper_2401_01728_amd as rv
+    dims, mb, tau = [4, 5, 3], 2, 1
+    g = rv.Stage.mlp(dims, mb, tau, 0.1)
+    w0 = kaiming_uniform_flat(7, dims); g.set_params(dev(w0))
+    x = torch.zeros(mb, 4, device="cuda"); dy = torch.ones(mb, 3, device="cuda")
+    g.forward(10, x); g.forward(11, x)
+    for bad, code in [(lambda: g.forward(12, x), rv.api.RV_E_STASH_FULL),
+                      (lambda: g.backward(99, dy), rv.api.RV_E_UNKNOWN_MB)]:
+        with pytest.raises(rv.RvError) as e:
+            bad()
+        assert e.value.status == code
+    g.backward(10, dy)
+    with pytest.raises(rv.RvError) as e:
+        g.forward(11, x)
+    assert e.value.status == rv.api.RV_E_DUP_MB
+    with pytest.raises(rv.RvError):
+        g.set_params(dev(w0))                      # a microbatch is still in flight
+    assert g.in_flight == 1
+    g.backward(11, dy)
+    assert g.in_flight == 0
