@@ -34,6 +34,13 @@ SYMBOLS = {
     "rv_strerror": (ctypes.c_char_p, [c_int]),
 }
 
+# per-kernel entry points declared in include/rv_kernels.h
+KERNEL_SYMBOLS = {
+    "rv_k_gemm_bf16": (c_int, [c_void_p, c_int64, c_int, c_void_p, c_int64, c_int, c_int, c_int, c_int, c_int,
+                               c_void_p, c_int64, c_void_p, c_void_p, c_void_p, c_int64, c_void_p, c_int,
+                               c_void_p]),
+}
+
 GEN_SYMBOLS = {
     "rvgen_fill_normal": (c_int, [c_void_p, c_uint64, c_uint32, c_uint32, c_float, c_float, c_uint64,
                                   c_float, c_int, c_void_p]),
@@ -59,7 +66,7 @@ def _load(path, table):
 def lib():
     global _lib
     if _lib is None:
-        _lib = _load(LIB_PATH, SYMBOLS)
+        _lib = _load(LIB_PATH, {**SYMBOLS, **KERNEL_SYMBOLS})
     return _lib
 
 

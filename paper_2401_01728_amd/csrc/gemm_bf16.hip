@@ -1,0 +1,318 @@
+// bf16 MFMA matrix products of the decoder stage (forward, dX and dW of every Linear),
+// fp32 accumulation, for gfx950.
+//
+//   C[M,N] = sum_k A(m,k) B(k,n)        K % 64 == 0, N % 8 == 0, M % 8 == 0
+//
+// Each operand is either "k-contiguous" (A[m*lda+k], B[n*ldb+k]) or "k-major"
+// (A[k*lda+m], B[k*ldb+n]).  The three products of a Linear y = x W, W stored [in,out]:
+//   forward  y  = x W      : A = x  k-contiguous, B = W  k-major
+//   dX       dx = dy W^T   : A = dy k-contiguous, B = W  k-contiguous (its rows are the n's)
+//   dW       dW = x^T dy   : A = x  k-major,      B = dy k-major      (contraction over tokens)
+//
+// Tiling: a workgroup of 256 lanes (2x2 waves) owns a BM x BN tile and walks K in steps
+// of 64.  Tiles are staged global -> registers -> LDS, double buffered, one barrier per
+// step.  A wave owns (BM/2) x (BN/2) as 32x32 MFMA tiles (v_mfma_f32_32x32x16_bf16).
+//   k-contiguous operands sit in LDS as [row][64 k] with a 144-byte row pitch, read as one
+//   16-byte fragment per lane;
+//   k-major operands sit as [64 k][cols] with pitch cols*2+64 bytes and are read with the
+//   LDS transpose read (ds_read_b64_tr_b16), which hands each lane four consecutive k of
+//   one column: no register transposes, no transposed copies of activations in HBM.
+// Both pitches make the reads bank-conflict free.
+// The MFMA is issued with the B fragment as its first operand, so a lane ends up with
+// four CONSECUTIVE n of one row m: epilogues store 8 (bf16) or 16 (fp32) bytes per lane.
+#include "internal.h"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int BK = 64;
+constexpr int kThreads = 256;
+constexpr int PITCH_KC = BK * 2 + 16;  // bytes per row of a k-contiguous tile
+
+__host__ __device__ constexpr int pitch_km(int cols) { return cols * 2 + 64; }
+__host__ __device__ constexpr int tile_bytes(bool km, int rows) {
+  return km ? BK * pitch_km(rows) : rows * PITCH_KC;
+}
+
+__device__ __forceinline__ float gelu_f(float z) {
+  return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f));
+}
+__device__ __forceinline__ float dgelu_f(float z) {
+  return 0.5f * (1.0f + erff(z * 0.70710678118654752f)) + z * 0.3989422804014327f * __expf(-0.5f * z * z);
+}
+
+// ---- global -> registers ---------------------------------------------------------------
+template <bool KM, int ROWS>
+struct Stage {
+  static constexpr int N = ROWS / 32;  // 16-byte chunks per lane
+  u32x4 v[N];
+};
+
+// rows: extent of the non-contraction dimension (M or N) of this operand, r0: tile origin
+template <bool KM, int ROWS>
+__device__ __forceinline__ void load_tile(Stage<KM, ROWS>& s, const uint16_t* __restrict__ g,
+                                          int64_t ld, int r0, int rows, int k0) {
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < Stage<KM, ROWS>::N; ++i) {
+    const int idx = t + kThreads * i;
+    if (!KM) {
+      int row = r0 + idx / 8, c = idx % 8;
+      row = row < rows ? row : rows - 1;
+      s.v[i] = *reinterpret_cast<const u32x4*>(g + (int64_t)row * ld + k0 + c * 8);
+    } else {
+      constexpr int CPR = ROWS / 8;
+      int kr = idx / CPR, c = idx % CPR;
+      int col = r0 + c * 8;
+      col = col < rows ? col : rows - 8;
+      s.v[i] = *reinterpret_cast<const u32x4*>(g + (int64_t)(k0 + kr) * ld + col);
+    }
+  }
+}
+
+template <bool KM, int ROWS>
+__device__ __forceinline__ void store_tile(const Stage<KM, ROWS>& s, char* lds) {
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int i = 0; i < Stage<KM, ROWS>::N; ++i) {
+    const int idx = t + kThreads * i;
+    if (!KM) {
+      int row = idx / 8, c = idx % 8;
+      *reinterpret_cast<u32x4*>(lds + row * PITCH_KC + c * 16) = s.v[i];
+    } else {
+      constexpr int CPR = ROWS / 8;
+      int kr = idx / CPR, c = idx % CPR;
+      *reinterpret_cast<u32x4*>(lds + kr * pitch_km(ROWS) + c * 16) = s.v[i];
+    }
+  }
+}
+
+// ---- LDS -> MFMA fragment ---------------------------------------------------------------
+// Fragment of 32 rows (row index = lane % 32) x 16 k (k = 8*(lane/32) .. +7) for k-step kk.
+template <bool KM, int ROWS>
+__device__ __forceinline__ bf16x8 read_frag(const char* lds, int row0, int kk) {
+  const int l = threadIdx.x & 63;
+  if (!KM) {
+    const char* p = lds + (row0 + (l & 31)) * PITCH_KC + kk * 32 + (l >> 5) * 16;
+    return *reinterpret_cast<const bf16x8*>(p);
+  } else {
+    const int q = l >> 4, i = l & 15;
+    const int kr = kk * 16 + 8 * (q >> 1) + (i >> 2);
+    const int col = row0 + 16 * (q & 1) + 4 * (i & 3);
+    const char* p = lds + kr * pitch_km(ROWS) + col * 2;
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (s16x4 __attribute__((address_space(3)))*)(p));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (s16x4 __attribute__((address_space(3)))*)(p + 4 * pitch_km(ROWS)));
+    s16x8 r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, r);
+  }
+}
+
+struct Epi {
+  void* out; int64_t ldo;
+  void* out2;
+  const uint16_t* bias;
+  const float* resid; int64_t ldr;
+  const uint16_t* zin;
+  float* part; // split-K partial sums
+};
+
+enum { EPI_BF16 = RV_EPI_BF16, EPI_BF16_BIAS = RV_EPI_BF16_BIAS, EPI_F32_BIAS_RESID = RV_EPI_F32_BIAS_RESID,
+       EPI_BF16_BIAS_GELU = RV_EPI_BF16_BIAS_GELU, EPI_BF16_DGELU = RV_EPI_BF16_DGELU, EPI_F32 = RV_EPI_F32,
+       EPI_F32_BIAS_RESID_BF16 = RV_EPI_F32_BIAS_RESID_BF16 };
+
+template <int EPI>
+__device__ __forceinline__ void epilogue4(const Epi& e, int m, int n, f32x4 a) {
+  // four consecutive columns n..n+3 of row m
+  if (EPI == EPI_BF16_BIAS || EPI == EPI_F32_BIAS_RESID || EPI == EPI_BF16_BIAS_GELU ||
+      EPI == EPI_F32_BIAS_RESID_BF16) {
+    u32x2 b = *reinterpret_cast<const u32x2*>(e.bias + n);
+    a.x += __uint_as_float(b.x << 16); a.y += __uint_as_float(b.x & 0xFFFF0000u);
+    a.z += __uint_as_float(b.y << 16); a.w += __uint_as_float(b.y & 0xFFFF0000u);
+  }
+  if (EPI == EPI_BF16 || EPI == EPI_BF16_BIAS) {
+    u32x2 o; o.x = rv_pack_bf16x2(a.x, a.y); o.y = rv_pack_bf16x2(a.z, a.w);
+    *reinterpret_cast<u32x2*>((uint16_t*)e.out + (int64_t)m * e.ldo + n) = o;
+  } else if (EPI == EPI_F32_BIAS_RESID || EPI == EPI_F32_BIAS_RESID_BF16) {
+    f32x4 r = *reinterpret_cast<const f32x4*>(e.resid + (int64_t)m * e.ldr + n);
+    a += r;
+    *reinterpret_cast<f32x4*>((float*)e.out + (int64_t)m * e.ldo + n) = a;
+    if (EPI == EPI_F32_BIAS_RESID_BF16) {
+      u32x2 o; o.x = rv_pack_bf16x2(a.x, a.y); o.y = rv_pack_bf16x2(a.z, a.w);
+      *reinterpret_cast<u32x2*>((uint16_t*)e.out2 + (int64_t)m * e.ldo + n) = o;
+    }
+  } else if (EPI == EPI_BF16_BIAS_GELU) {
+    u32x2 o; o.x = rv_pack_bf16x2(a.x, a.y); o.y = rv_pack_bf16x2(a.z, a.w);
+    *reinterpret_cast<u32x2*>((uint16_t*)e.out + (int64_t)m * e.ldo + n) = o;
+    u32x2 g;
+    g.x = rv_pack_bf16x2(gelu_f(a.x), gelu_f(a.y));
+    g.y = rv_pack_bf16x2(gelu_f(a.z), gelu_f(a.w));
+    *reinterpret_cast<u32x2*>((uint16_t*)e.out2 + (int64_t)m * e.ldo + n) = g;
+  } else if (EPI == EPI_BF16_DGELU) {
+    u32x2 z = *reinterpret_cast<const u32x2*>(e.zin + (int64_t)m * e.ldo + n);
+    a.x *= dgelu_f(__uint_as_float(z.x << 16)); a.y *= dgelu_f(__uint_as_float(z.x & 0xFFFF0000u));
+    a.z *= dgelu_f(__uint_as_float(z.y << 16)); a.w *= dgelu_f(__uint_as_float(z.y & 0xFFFF0000u));
+    u32x2 o; o.x = rv_pack_bf16x2(a.x, a.y); o.y = rv_pack_bf16x2(a.z, a.w);
+    *reinterpret_cast<u32x2*>((uint16_t*)e.out + (int64_t)m * e.ldo + n) = o;
+  } else if (EPI == EPI_F32) {
+    *reinterpret_cast<f32x4*>((float*)e.out + (int64_t)m * e.ldo + n) = a;
+  }
+}
+
+template <int BM, int BN, bool AKM, bool BKM, int EPI>
+__global__ __launch_bounds__(kThreads) void gemm_kernel(const uint16_t* __restrict__ A, int64_t lda,
+                                                        const uint16_t* __restrict__ B, int64_t ldb,
+                                                        int M, int N, int K, int tiles_m, Epi e) {
+  constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
+  constexpr int A_BYTES = tile_bytes(AKM, BM), B_BYTES = tile_bytes(BKM, BN);
+  extern __shared__ __align__(16) char smem[];
+  constexpr int BUF = A_BYTES + B_BYTES;   // buffer b: A tile at b*BUF, B tile behind it
+
+  // consecutive workgroups walk down a column of tiles: they share the B (weight) tile
+  const int bm = blockIdx.x % tiles_m, bn = blockIdx.x / tiles_m;
+  const int m0 = bm * BM, n0 = bn * BN;
+  const int wave = threadIdx.x >> 6, l = threadIdx.x & 63;
+  const int wm0 = (wave & 1) * WM, wn0 = (wave >> 1) * WN;
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  Stage<AKM, BM> sa;
+  Stage<BKM, BN> sb;
+  const int nk = K / BK;
+  load_tile<AKM, BM>(sa, A, lda, m0, M, 0);
+  load_tile<BKM, BN>(sb, B, ldb, n0, N, 0);
+  store_tile<AKM, BM>(sa, smem);
+  store_tile<BKM, BN>(sb, smem + A_BYTES);
+  __syncthreads();
+  for (int it = 0; it < nk; ++it) {
+    const int cur = it & 1;
+    const char* curA = smem + cur * BUF;
+    const char* curB = curA + A_BYTES;
+    if (it + 1 < nk) {
+      load_tile<AKM, BM>(sa, A, lda, m0, M, (it + 1) * BK);
+      load_tile<BKM, BN>(sb, B, ldb, n0, N, (it + 1) * BK);
+    }
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      bf16x8 fa[TM], fb[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) fa[i] = read_frag<AKM, BM>(curA, wm0 + i * 32, kk);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) fb[j] = read_frag<BKM, BN>(curB, wn0 + j * 32, kk);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+    }
+    if (it + 1 < nk) {
+      store_tile<AKM, BM>(sa, smem + (cur ^ 1) * BUF);
+      store_tile<BKM, BN>(sb, smem + (cur ^ 1) * BUF + A_BYTES);
+    }
+    __syncthreads();
+  }
+
+  // lane holds row m = l%32 of the wave tile and, per group rg of 4 registers,
+  // columns 8*rg + 4*(l/32) .. +3
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int m = m0 + wm0 + i * 32 + (l & 31);
+    if (m >= M) continue;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+#pragma unroll
+      for (int rg = 0; rg < 4; ++rg) {
+        const int n = n0 + wn0 + j * 32 + 8 * rg + 4 * (l >> 5);
+        if (n >= N) continue;
+        f32x4 a = {acc[i][j][4 * rg], acc[i][j][4 * rg + 1], acc[i][j][4 * rg + 2], acc[i][j][4 * rg + 3]};
+        epilogue4<EPI>(e, m, n, a);
+      }
+    }
+  }
+}
+
+template <int BM, int BN, bool AKM, bool BKM, int EPI>
+rv_status launch(const rv_gemm_args& g, hipStream_t st) {
+  constexpr int smem = 2 * (tile_bytes(AKM, BM) + tile_bytes(BKM, BN));
+  static bool configured = false;
+  auto kern = gemm_kernel<BM, BN, AKM, BKM, EPI>;
+  if (!configured) {
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
+      return RV_E_DEVICE;
+    configured = true;
+  }
+  const int tm = (g.M + BM - 1) / BM, tn = (g.N + BN - 1) / BN;
+  Epi e{g.out, g.ldo, g.out2, g.bias, g.resid, g.ldr, g.zin, nullptr};
+  hipLaunchKernelGGL(kern, dim3(tm * tn), dim3(kThreads), smem, st, g.A, g.lda, g.B, g.ldb, g.M, g.N, g.K,
+                     tm, e);
+  return rv_launch_status();
+}
+
+template <bool AKM, bool BKM, int EPI>
+rv_status pick_tile(const rv_gemm_args& g, hipStream_t st) {
+  // the largest tile that still gives every CU a workgroup
+  const long t256 = (long)((g.M + 255) / 256) * ((g.N + 255) / 256);
+  const long t128 = (long)((g.M + 127) / 128) * ((g.N + 127) / 128);
+  if (g.tile == 256 || (g.tile == 0 && t256 >= 200)) return launch<256, 256, AKM, BKM, EPI>(g, st);
+  (void)t128;
+  return launch<128, 128, AKM, BKM, EPI>(g, st);
+}
+
+}  // namespace
+
+rv_status rv_gemm_bf16(const rv_gemm_args& g, hipStream_t st) {
+  if (!g.A || !g.B || !g.out || g.M < 8 || g.N < 8 || g.K < BK) return RV_E_INVAL;
+  if (g.K % BK || g.N % 8 || g.M % 8 || g.lda % 8 || g.ldb % 8 || g.ldo % 4) return RV_E_INVAL;
+  if ((((uintptr_t)g.A) | ((uintptr_t)g.B) | ((uintptr_t)g.out)) & 15) return RV_E_INVAL;
+  const bool need_bias = g.epi == EPI_BF16_BIAS || g.epi == EPI_F32_BIAS_RESID ||
+                         g.epi == EPI_BF16_BIAS_GELU || g.epi == EPI_F32_BIAS_RESID_BF16;
+  if (need_bias && (!g.bias || (((uintptr_t)g.bias) & 7))) return RV_E_INVAL;
+  if ((g.epi == EPI_F32_BIAS_RESID || g.epi == EPI_F32_BIAS_RESID_BF16) &&
+      (!g.resid || g.ldr % 4 || (((uintptr_t)g.resid) & 15)))
+    return RV_E_INVAL;
+  if ((g.epi == EPI_BF16_BIAS_GELU || g.epi == EPI_F32_BIAS_RESID_BF16) && !g.out2) return RV_E_INVAL;
+  if (g.epi == EPI_BF16_DGELU && !g.zin) return RV_E_INVAL;
+  // only the layout/epilogue pairs the stage uses are instantiated
+  if (!g.a_kmajor && g.b_kmajor) {          // forward products
+    switch (g.epi) {
+      case EPI_BF16_BIAS: return pick_tile<false, true, EPI_BF16_BIAS>(g, st);
+      case EPI_F32_BIAS_RESID: return pick_tile<false, true, EPI_F32_BIAS_RESID>(g, st);
+      case EPI_F32_BIAS_RESID_BF16: return pick_tile<false, true, EPI_F32_BIAS_RESID_BF16>(g, st);
+      case EPI_BF16_BIAS_GELU: return pick_tile<false, true, EPI_BF16_BIAS_GELU>(g, st);
+    }
+  } else if (!g.a_kmajor && !g.b_kmajor) {  // input-gradient products
+    switch (g.epi) {
+      case EPI_BF16: return pick_tile<false, false, EPI_BF16>(g, st);
+      case EPI_BF16_DGELU: return pick_tile<false, false, EPI_BF16_DGELU>(g, st);
+    }
+  } else if (g.a_kmajor && g.b_kmajor) {    // weight-gradient products
+    if (g.epi == EPI_F32) return pick_tile<true, true, EPI_F32>(g, st);
+  }
+  return RV_E_INVAL;
+}
+
+extern "C" rv_status rv_k_gemm_bf16(const void* A, int64_t lda, int a_kmajor, const void* B, int64_t ldb,
+                                    int b_kmajor, int M, int N, int K, int epilogue, void* out, int64_t ldo,
+                                    void* out2, const void* bias, const float* resid, int64_t ldr,
+                                    const void* zin, int tile, void* stream) {
+  rv_gemm_args g;
+  g.A = (const uint16_t*)A; g.lda = lda; g.a_kmajor = a_kmajor;
+  g.B = (const uint16_t*)B; g.ldb = ldb; g.b_kmajor = b_kmajor;
+  g.M = M; g.N = N; g.K = K; g.epi = epilogue; g.out = out; g.ldo = ldo; g.out2 = out2;
+  g.bias = (const uint16_t*)bias; g.resid = resid; g.ldr = ldr; g.zin = (const uint16_t*)zin; g.tile = tile;
+  return rv_gemm_bf16(g, (hipStream_t)stream);
+}

@@ -9,6 +9,22 @@ rv_status rv_launch_update(float* w, const float* g, size_t n, float eta, void* 
                            hipStream_t st);
 rv_status rv_launch_publish(const float* w, size_t n, void* copy, int copy_kind, hipStream_t st);
 
+// ---- gemm_bf16.hip ----------------------------------------------------------------
+#include "../../include/rv_kernels.h"
+struct rv_gemm_args {
+  const uint16_t* A = nullptr; int64_t lda = 0; int a_kmajor = 0;
+  const uint16_t* B = nullptr; int64_t ldb = 0; int b_kmajor = 0;
+  int M = 0, N = 0, K = 0;
+  int epi = 0;
+  void* out = nullptr; int64_t ldo = 0;   // primary output [M, ldo]
+  void* out2 = nullptr;                   // second output, same pitch (GELU value / bf16 copy)
+  const uint16_t* bias = nullptr;         // bf16 [N]
+  const float* resid = nullptr; int64_t ldr = 0;
+  const uint16_t* zin = nullptr;          // bf16 [M, ldo] pre-activations for GELU'
+  int tile = 0;                           // 0 = choose, 128 or 256 = force
+};
+rv_status rv_gemm_bf16(const rv_gemm_args& g, hipStream_t st);
+
 // ---- stage bookkeeping -------------------------------------------------------------
 struct rv_slot {
   bool live = false;

@@ -8,19 +8,20 @@ from paper_2401_01728_amd import _lib
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared():
-    text = open(os.path.join(ROOT, "include", "rv.h")).read()
+def _declared(header="rv.h"):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(rv_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(rv_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_header_and_binding_agree():
     assert _declared() == sorted(_lib.SYMBOLS)
+    assert _declared("rv_kernels.h") == sorted(_lib.KERNEL_SYMBOLS)
 
 
 def test_library_exports_every_symbol():
     lib = _lib.lib()
-    for name in _declared():
+    for name in _declared() + _declared("rv_kernels.h"):
         assert getattr(lib, name) is not None
 
 
