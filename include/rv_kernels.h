@@ -38,6 +38,47 @@ rv_status rv_k_gemm_bf16(const void* A, int64_t lda, int a_kmajor, const void* B
                          void* out2, const void* bias, const float* resid, int64_t ldr,
                          const void* zin, int tile, void* stream);
 
+/*
+ * LayerNorm over the last dimension (biased variance, eps inside the root), affine in
+ * bf16: y bf16 [T,d] = (x - mean) * rstd * gamma + beta; mean, rstd fp32 [T] are kept for
+ * the backward.  x is fp32 [T,d], or bf16 when x_is_bf16 (then xcopy receives it widened
+ * to fp32).  d % 4 == 0, d <= 8192.
+ */
+rv_status rv_k_layernorm_fwd(const void* x, int x_is_bf16, float* xcopy, const void* gamma,
+                             const void* beta, void* y, float* mean, float* rstd, int T, int d,
+                             float eps, void* stream);
+
+/*
+ * Backward of the LayerNorm joined with the residual branch it hangs off:
+ *   dx = dres + rstd * (dxh - mean(dxh) - xh * mean(dxh * xh)),  dxh = dy * gamma
+ * dy bf16 [T,d]; x, dres, dx fp32 [T,d] (dx may alias dres); dx_bf16 optional bf16 copy.
+ * Column sums over tokens: dgamma = sum dy*xh, dbeta = sum dy, dbias = sum dx (each fp32
+ * [d], each optional).  part: scratch of ceil(T/16)*3*d floats.  d <= 4096.
+ */
+rv_status rv_k_layernorm_bwd(const void* dy, const float* x, const float* mean, const float* rstd,
+                             const void* gamma, const float* dres, float* dx, void* dx_bf16,
+                             float* part, float* dgamma, float* dbeta, float* dbias, int T, int d,
+                             void* stream);
+
+/* out fp32 [N] = column sums of a bf16 [T,N] matrix (row pitch lda); part: scratch of
+ * ceil(T/128)*N floats.  N, lda % 8 == 0. */
+rv_status rv_k_colsum_bf16(const void* a, int64_t lda, int T, int N, float* part, float* out,
+                           void* stream);
+
+/*
+ * Causal self-attention.  qkv bf16 [microbatch*seq, 3*d_model] (column thirds q|k|v, heads
+ * contiguous inside a third); out bf16 [microbatch*seq, d_model];
+ * lse2 fp32 [microbatch, n_heads, seq] = log2 of the softmax denominator in the scaled
+ * base-2 domain (kept for the backward).  d_model/n_heads in {64,128}, seq % 64 == 0.
+ */
+rv_status rv_k_attention_fwd(const void* qkv, void* out, float* lse2, int microbatch, int seq,
+                             int d_model, int n_heads, void* stream);
+/* Gradient of the above: dout bf16 [T,d_model] -> dqkv bf16 [T,3*d_model];
+ * dscratch: fp32 [microbatch*n_heads*seq]. */
+rv_status rv_k_attention_bwd(const void* qkv, const void* out, const void* dout, const float* lse2,
+                             float* dscratch, void* dqkv, int microbatch, int seq, int d_model,
+                             int n_heads, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

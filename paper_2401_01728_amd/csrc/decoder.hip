@@ -1,6 +1,206 @@
-// placeholder until the decoder kernels land
+// Decoder stage: L pre-LayerNorm transformer blocks as one peer's forward_pass and its
+// exact gradient at the stashed weight version (paper Alg. 1; Eq. 2).  Host-side
+// sequencing only; the work is in gemm_bf16.hip, attention.hip and norm.hip.
+//
+//   u  = LN1(x);  qkv = u Wqkv + bqkv;  a = CausalSoftmax(q k^T / sqrt(dh)) v
+//   x1 = x + a Wo + bo;   v2 = LN2(x1);  z = v2 W1 + b1;  g = GELU(z);  y = x1 + g W2 + b2
+//
+// The residual stream (x, x1, y) and its gradient are fp32 inside the stage; matrix
+// product operands are bf16.  Per microbatch and block the stash keeps x, x1 (fp32), the
+// LN statistics, u, qkv, a, v2, z, g (bf16) and the softmax log-sums: everything the
+// backward reads, so nothing is recomputed except the attention probabilities.
+#include <new>
 #include "internal.h"
-rv_status rv_dec_plan(rv_stage*) { return RV_E_INVAL; }
-void rv_dec_free(rv_stage*) {}
-rv_status rv_dec_forward(rv_stage*, rv_slot&, const void*, void*) { return RV_E_INVAL; }
-rv_status rv_dec_backward(rv_stage*, rv_slot&, const void*, void*) { return RV_E_INVAL; }
+
+namespace {
+
+size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct DecPlan {
+  int L, d, H, f, S, mb, T;
+  // element offsets inside one block's parameters (same in the fp32 master and the bf16 version)
+  size_t ln1g, ln1b, wqkv, bqkv, wo, bo, ln2g, ln2b, w1, b1, w2, b2, per_block;
+  // byte offsets inside one block's stash
+  size_t s_x, s_m1, s_r1, s_u, s_qkv, s_a, s_lse, s_x1, s_m2, s_r2, s_v2, s_z, s_g, blk_bytes;
+  // byte offsets inside the work buffer
+  size_t w_dres, w_dres16, w_dtmp, w_dz, w_dqkv, w_D, w_part, w_ytmp;
+};
+
+}  // namespace
+
+rv_status rv_dec_plan(rv_stage* s) {
+  const int64_t d = s->dims[0], H = s->dims[1], f = s->dims[2], S = s->dims[3];
+  if (d < 64 || d > 4096 || d % 64 || H < 1 || d % H || f < 64 || f % 64 || f > (1 << 16) || S < 64 ||
+      S % 64 || S > (1 << 16))
+    return RV_E_INVAL;
+  const int64_t dh = d / H;
+  if (dh != 64 && dh != 128) return RV_E_INVAL;
+  if ((int64_t)s->microbatch * S > (1 << 24)) return RV_E_INVAL;
+  DecPlan* p = new (std::nothrow) DecPlan();
+  if (!p) return RV_E_NOMEM;
+  s->impl = p;
+  p->L = s->n_layers; p->d = (int)d; p->H = (int)H; p->f = (int)f; p->S = (int)S; p->mb = s->microbatch;
+  p->T = p->mb * p->S;
+  size_t o = 0;
+  p->ln1g = o; o += d; p->ln1b = o; o += d;
+  p->wqkv = o; o += (size_t)d * 3 * d; p->bqkv = o; o += 3 * d;
+  p->wo = o; o += (size_t)d * d; p->bo = o; o += d;
+  p->ln2g = o; o += d; p->ln2b = o; o += d;
+  p->w1 = o; o += (size_t)d * f; p->b1 = o; o += f;
+  p->w2 = o; o += (size_t)f * d; p->b2 = o; o += d;
+  p->per_block = o;
+  s->P = o * p->L;
+  const size_t T = p->T;
+  size_t b = 0;
+  p->s_x = b; b += align_up(T * d * 4);
+  p->s_m1 = b; b += align_up(T * 4); p->s_r1 = b; b += align_up(T * 4);
+  p->s_u = b; b += align_up(T * d * 2);
+  p->s_qkv = b; b += align_up(T * 3 * d * 2);
+  p->s_a = b; b += align_up(T * d * 2);
+  p->s_lse = b; b += align_up(T * H * 4);
+  p->s_x1 = b; b += align_up(T * d * 4);
+  p->s_m2 = b; b += align_up(T * 4); p->s_r2 = b; b += align_up(T * 4);
+  p->s_v2 = b; b += align_up(T * d * 2);
+  p->s_z = b; b += align_up(T * f * 2);
+  p->s_g = b; b += align_up(T * f * 2);
+  p->blk_bytes = b;
+  s->slot_bytes = b * p->L;
+  size_t w = 0;
+  p->w_dres = w; w += align_up(T * d * 4);
+  p->w_dres16 = w; w += align_up(T * d * 2);
+  p->w_dtmp = w; w += align_up(T * d * 2);
+  p->w_dz = w; w += align_up(T * f * 2);
+  p->w_dqkv = w; w += align_up(T * 3 * d * 2);
+  p->w_D = w; w += align_up(T * H * 4);
+  const size_t part_ln = (size_t)rv_ln_bwd_parts(p->T) * 3 * d;
+  const size_t part_cs = (size_t)rv_colsum_parts(p->T) * (size_t)std::max<int64_t>(3 * d, f);
+  p->w_part = w; w += align_up(std::max(part_ln, part_cs) * 4);
+  p->w_ytmp = w; w += align_up(T * d * 4);
+  s->work_bytes = w;
+  return RV_OK;
+}
+
+void rv_dec_free(rv_stage* s) {
+  delete (DecPlan*)s->impl;
+  s->impl = nullptr;
+}
+
+namespace {
+
+rv_status gemm(hipStream_t st, const void* A, int64_t lda, int akm, const void* B, int64_t ldb, int bkm, int M,
+               int N, int K, int epi, void* out, int64_t ldo, void* out2 = nullptr, const void* bias = nullptr,
+               const float* resid = nullptr, const void* zin = nullptr) {
+  rv_gemm_args g;
+  g.A = (const uint16_t*)A; g.lda = lda; g.a_kmajor = akm;
+  g.B = (const uint16_t*)B; g.ldb = ldb; g.b_kmajor = bkm;
+  g.M = M; g.N = N; g.K = K; g.epi = epi; g.out = out; g.ldo = ldo; g.out2 = out2;
+  g.bias = (const uint16_t*)bias; g.resid = resid; g.ldr = ldo; g.zin = (const uint16_t*)zin;
+  return rv_gemm_bf16(g, st);
+}
+
+}  // namespace
+
+rv_status rv_dec_forward(rv_stage* s, rv_slot& slot, const void* in, void* out) {
+  const DecPlan& p = *(const DecPlan*)s->impl;
+  const uint16_t* wv = (const uint16_t*)s->ver[slot.ver];
+  hipStream_t st = s->st;
+  const int T = p.T, d = p.d, f = p.f;
+  for (int l = 0; l < p.L; ++l) {
+    const uint16_t* w = wv + (size_t)l * p.per_block;
+    char* sb = slot.base + (size_t)l * p.blk_bytes;
+    float* x = (float*)(sb + p.s_x);
+    float* x1 = (float*)(sb + p.s_x1);
+    uint16_t* u = (uint16_t*)(sb + p.s_u);
+    uint16_t* qkv = (uint16_t*)(sb + p.s_qkv);
+    uint16_t* a = (uint16_t*)(sb + p.s_a);
+    uint16_t* v2 = (uint16_t*)(sb + p.s_v2);
+    uint16_t* z = (uint16_t*)(sb + p.s_z);
+    uint16_t* g = (uint16_t*)(sb + p.s_g);
+    if (l == 0)
+      RV_TRY(rv_ln_fwd(in, 1, x, w + p.ln1g, w + p.ln1b, u, (float*)(sb + p.s_m1), (float*)(sb + p.s_r1), T, d,
+                       s->ln_eps, st));
+    else
+      RV_TRY(rv_ln_fwd(x, 0, nullptr, w + p.ln1g, w + p.ln1b, u, (float*)(sb + p.s_m1), (float*)(sb + p.s_r1), T,
+                       d, s->ln_eps, st));
+    RV_TRY(gemm(st, u, d, 0, w + p.wqkv, 3 * d, 1, T, 3 * d, d, RV_EPI_BF16_BIAS, qkv, 3 * d, nullptr, w + p.bqkv));
+    RV_TRY(rv_attn_fwd(qkv, a, (float*)(sb + p.s_lse), p.mb, p.S, d, p.H, st));
+    RV_TRY(gemm(st, a, d, 0, w + p.wo, d, 1, T, d, d, RV_EPI_F32_BIAS_RESID, x1, d, nullptr, w + p.bo, x));
+    RV_TRY(rv_ln_fwd(x1, 0, nullptr, w + p.ln2g, w + p.ln2b, v2, (float*)(sb + p.s_m2), (float*)(sb + p.s_r2), T, d,
+                     s->ln_eps, st));
+    RV_TRY(gemm(st, v2, d, 0, w + p.w1, f, 1, T, f, d, RV_EPI_BF16_BIAS_GELU, z, f, g, w + p.b1));
+    if (l + 1 < p.L) {
+      float* xn = (float*)(slot.base + (size_t)(l + 1) * p.blk_bytes + p.s_x);
+      RV_TRY(gemm(st, g, f, 0, w + p.w2, d, 1, T, d, f, RV_EPI_F32_BIAS_RESID, xn, d, nullptr, w + p.b2, x1));
+    } else {
+      RV_TRY(gemm(st, g, f, 0, w + p.w2, d, 1, T, d, f, RV_EPI_F32_BIAS_RESID_BF16, s->work + p.w_ytmp, d, out,
+                  w + p.b2, x1));
+    }
+  }
+  return RV_OK;
+}
+
+rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void* grad_in) {
+  const DecPlan& p = *(const DecPlan*)s->impl;
+  const uint16_t* wv = (const uint16_t*)s->ver[slot.ver];
+  hipStream_t st = s->st;
+  const int T = p.T, d = p.d, f = p.f;
+  float* dres = (float*)(s->work + p.w_dres);
+  uint16_t* dres16_buf = (uint16_t*)(s->work + p.w_dres16);
+  uint16_t* dtmp = (uint16_t*)(s->work + p.w_dtmp);
+  uint16_t* dz = (uint16_t*)(s->work + p.w_dz);
+  uint16_t* dqkv = (uint16_t*)(s->work + p.w_dqkv);
+  float* Dbuf = (float*)(s->work + p.w_D);
+  float* part = (float*)(s->work + p.w_part);
+  const int ln_parts = rv_ln_bwd_parts(T), cs_parts = rv_colsum_parts(T);
+
+  // gradient of the last block's output: fp32 copy for the residual path, bf16 as operand
+  RV_TRY(rv_bf16_to_f32((const uint16_t*)grad_out, dres, (int64_t)T * d, st));
+  const uint16_t* dres16 = (const uint16_t*)grad_out;
+  {
+    float* gl = s->grad + (size_t)(p.L - 1) * p.per_block;
+    RV_TRY(rv_colsum_bf16(dres16, d, T, d, part, st));
+    RV_TRY(rv_reduce_rows(part, cs_parts, d, d, gl + p.b2, st));
+  }
+  for (int l = p.L - 1; l >= 0; --l) {
+    const uint16_t* w = wv + (size_t)l * p.per_block;
+    float* gl = s->grad + (size_t)l * p.per_block;
+    const char* sb = slot.base + (size_t)l * p.blk_bytes;
+    const float* x = (const float*)(sb + p.s_x);
+    const float* x1 = (const float*)(sb + p.s_x1);
+    const uint16_t* u = (const uint16_t*)(sb + p.s_u);
+    const uint16_t* qkv = (const uint16_t*)(sb + p.s_qkv);
+    const uint16_t* a = (const uint16_t*)(sb + p.s_a);
+    const uint16_t* v2 = (const uint16_t*)(sb + p.s_v2);
+    const uint16_t* z = (const uint16_t*)(sb + p.s_z);
+    const uint16_t* g = (const uint16_t*)(sb + p.s_g);
+    // feed-forward half
+    RV_TRY(gemm(st, g, f, 1, dres16, d, 1, f, d, T, RV_EPI_F32, gl + p.w2, d));                      // dW2 = g^T dy
+    RV_TRY(gemm(st, dres16, d, 0, w + p.w2, d, 0, T, f, d, RV_EPI_BF16_DGELU, dz, f, nullptr, nullptr, nullptr, z));
+    RV_TRY(gemm(st, v2, d, 1, dz, f, 1, d, f, T, RV_EPI_F32, gl + p.w1, f));                         // dW1 = v2^T dz
+    RV_TRY(rv_colsum_bf16(dz, f, T, f, part, st));
+    RV_TRY(rv_reduce_rows(part, cs_parts, f, f, gl + p.b1, st));
+    RV_TRY(gemm(st, dz, f, 0, w + p.w1, f, 0, T, d, f, RV_EPI_BF16, dtmp, d));                       // dv2 = dz W1^T
+    RV_TRY(rv_ln_bwd(dtmp, x1, (const float*)(sb + p.s_m2), (const float*)(sb + p.s_r2), w + p.ln2g, dres, dres,
+                     dres16_buf, part, T, d, st));
+    dres16 = dres16_buf;
+    RV_TRY(rv_reduce_rows(part, ln_parts, 3 * (int64_t)d, d, gl + p.ln2g, st));
+    RV_TRY(rv_reduce_rows(part + d, ln_parts, 3 * (int64_t)d, d, gl + p.ln2b, st));
+    RV_TRY(rv_reduce_rows(part + 2 * d, ln_parts, 3 * (int64_t)d, d, gl + p.bo, st));               // dbo = sum dx1
+    // attention half
+    RV_TRY(gemm(st, a, d, 1, dres16, d, 1, d, d, T, RV_EPI_F32, gl + p.wo, d));                      // dWo = a^T dx1
+    RV_TRY(gemm(st, dres16, d, 0, w + p.wo, d, 0, T, d, d, RV_EPI_BF16, dtmp, d));                   // da = dx1 Wo^T
+    RV_TRY(rv_attn_bwd(qkv, a, dtmp, (const float*)(sb + p.s_lse), Dbuf, dqkv, p.mb, p.S, d, p.H, st));
+    RV_TRY(gemm(st, u, d, 1, dqkv, 3 * d, 1, d, 3 * d, T, RV_EPI_F32, gl + p.wqkv, 3 * d));          // dWqkv
+    RV_TRY(rv_colsum_bf16(dqkv, 3 * d, T, 3 * d, part, st));
+    RV_TRY(rv_reduce_rows(part, cs_parts, 3 * d, 3 * d, gl + p.bqkv, st));
+    RV_TRY(gemm(st, dqkv, 3 * d, 0, w + p.wqkv, 3 * d, 0, T, d, 3 * d, RV_EPI_BF16, dtmp, d));       // du
+    uint16_t* dx16 = l == 0 ? (uint16_t*)grad_in : dres16_buf;
+    RV_TRY(rv_ln_bwd(dtmp, x, (const float*)(sb + p.s_m1), (const float*)(sb + p.s_r1), w + p.ln1g, dres, dres, dx16,
+                     part, T, d, st));
+    RV_TRY(rv_reduce_rows(part, ln_parts, 3 * (int64_t)d, d, gl + p.ln1g, st));
+    RV_TRY(rv_reduce_rows(part + d, ln_parts, 3 * (int64_t)d, d, gl + p.ln1b, st));
+    if (l > 0)  // the residual gradient leaving this block is dy of the block below: its b2 gradient
+      RV_TRY(rv_reduce_rows(part + 2 * d, ln_parts, 3 * (int64_t)d, d, s->grad + (size_t)(l - 1) * p.per_block + p.b2, st));
+  }
+  return RV_OK;
+}

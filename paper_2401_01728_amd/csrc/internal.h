@@ -25,6 +25,24 @@ struct rv_gemm_args {
 };
 rv_status rv_gemm_bf16(const rv_gemm_args& g, hipStream_t st);
 
+// ---- norm.hip ---------------------------------------------------------------------
+rv_status rv_ln_fwd(const void* x, int x_is_bf16, float* xcopy, const uint16_t* gamma, const uint16_t* beta,
+                    uint16_t* y, float* mean, float* rstd, int T, int d, float eps, hipStream_t st);
+int rv_ln_bwd_parts(int T);   // partial rows written by rv_ln_bwd (each 3*d floats)
+rv_status rv_ln_bwd(const uint16_t* dy, const float* x, const float* mean, const float* rstd,
+                    const uint16_t* gamma, const float* dres, float* dx, uint16_t* dx_bf16, float* part,
+                    int T, int d, hipStream_t st);
+int rv_colsum_parts(int T);   // partial rows written by rv_colsum_bf16 (each N floats)
+rv_status rv_colsum_bf16(const uint16_t* a, int64_t lda, int T, int N, float* part, hipStream_t st);
+rv_status rv_reduce_rows(const float* part, int R, int64_t pitch, int N, float* out, hipStream_t st);
+rv_status rv_bf16_to_f32(const uint16_t* a, float* o, int64_t n, hipStream_t st);
+
+// ---- attention.hip ----------------------------------------------------------------
+rv_status rv_attn_fwd(const uint16_t* qkv, uint16_t* out, float* lse2, int mb, int S, int d, int H,
+                      hipStream_t st);
+rv_status rv_attn_bwd(const uint16_t* qkv, const uint16_t* out, const uint16_t* dout, const float* lse2,
+                      float* Dbuf, uint16_t* dqkv, int mb, int S, int d, int H, hipStream_t st);
+
 // ---- stage bookkeeping -------------------------------------------------------------
 struct rv_slot {
   bool live = false;

@@ -1,0 +1,313 @@
+// LayerNorm forward / backward and the column reductions behind bias and LN-affine
+// gradients of the decoder block (pieces of a peer's forward_pass and of its exact
+// gradient, paper Alg. 1 / Eq. 2).  All HBM-bound: one wave owns a token row, a lane owns
+// 16-byte column groups lane*4 + 256*i, statistics are reduced with wave shuffles, the
+// residual stream and its gradient stay fp32, matrix-product operands leave as bf16.
+//
+// Column sums over tokens are produced in two deterministic steps: every workgroup
+// writes one partial row, a second kernel adds the partial rows in order.
+#include "internal.h"
+
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 256;
+constexpr int kWaves = 4;
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+__device__ __forceinline__ f32x4 bf16x4_to_f32(u32x2 b) {
+  f32x4 r;
+  r.x = __uint_as_float(b.x << 16); r.y = __uint_as_float(b.x & 0xFFFF0000u);
+  r.z = __uint_as_float(b.y << 16); r.w = __uint_as_float(b.y & 0xFFFF0000u);
+  return r;
+}
+__device__ __forceinline__ u32x2 f32_to_bf16x4(f32x4 a) {
+  u32x2 o; o.x = rv_pack_bf16x2(a.x, a.y); o.y = rv_pack_bf16x2(a.z, a.w);
+  return o;
+}
+
+// y = LN(x) * gamma + beta.  IN_BF16: x arrives as bf16 (stage input) and is also written
+// out as the fp32 residual stream xcopy.
+template <int NV, bool IN_BF16>
+__global__ __launch_bounds__(kThreads) void ln_fwd_kernel(const void* __restrict__ xin,
+                                                          float* __restrict__ xcopy,
+                                                          const uint16_t* __restrict__ gamma,
+                                                          const uint16_t* __restrict__ beta,
+                                                          uint16_t* __restrict__ y,
+                                                          float* __restrict__ mean,
+                                                          float* __restrict__ rstd, int T, int d,
+                                                          float eps) {
+  const int wave = threadIdx.x >> 6, l = threadIdx.x & 63;
+  const int row = blockIdx.x * kWaves + wave;
+  if (row >= T) return;
+  f32x4 v[NV];
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = l * 4 + 256 * i;
+    if (c < d) {
+      if (IN_BF16) {
+        v[i] = bf16x4_to_f32(*reinterpret_cast<const u32x2*>((const uint16_t*)xin + (int64_t)row * d + c));
+        *reinterpret_cast<f32x4*>(xcopy + (int64_t)row * d + c) = v[i];
+      } else {
+        v[i] = *reinterpret_cast<const f32x4*>((const float*)xin + (int64_t)row * d + c);
+      }
+      s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+    }
+  }
+  const float mu = wave_sum(s) / (float)d;
+  float q = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = l * 4 + 256 * i;
+    if (c < d) {
+      f32x4 t = v[i] - mu;
+      q += (t.x * t.x + t.y * t.y) + (t.z * t.z + t.w * t.w);
+    }
+  }
+  const float r = rsqrtf(wave_sum(q) / (float)d + eps);
+  if (l == 0) { mean[row] = mu; rstd[row] = r; }
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = l * 4 + 256 * i;
+    if (c < d) {
+      f32x4 g = bf16x4_to_f32(*reinterpret_cast<const u32x2*>(gamma + c));
+      f32x4 b = bf16x4_to_f32(*reinterpret_cast<const u32x2*>(beta + c));
+      f32x4 o = (v[i] - mu) * r * g + b;
+      *reinterpret_cast<u32x2*>(y + (int64_t)row * d + c) = f32_to_bf16x4(o);
+    }
+  }
+}
+
+// Backward of y = LN(x)*gamma + beta joined with the residual branch:
+//   dx = dres + rstd * (dxh - mean(dxh) - xh * mean(dxh * xh)),  dxh = dy * gamma
+// Writes dx (fp32, may alias dres) and optionally its bf16 rounding; accumulates three
+// column sums over the workgroup's rows into part[blk][0..2][d]:
+//   0: sum dy * xh (d gamma)   1: sum dy (d beta)   2: sum dx (bias gradient of the Linear
+//   whose output fed this residual stream).
+constexpr int kRowsPerBlock = 16;
+
+template <int NV>
+__global__ __launch_bounds__(kThreads) void ln_bwd_kernel(const uint16_t* __restrict__ dy,
+                                                          const float* __restrict__ x,
+                                                          const float* __restrict__ mean,
+                                                          const float* __restrict__ rstd,
+                                                          const uint16_t* __restrict__ gamma,
+                                                          const float* dres, float* dx,
+                                                          uint16_t* __restrict__ dx_bf16,
+                                                          float* __restrict__ part, int T, int d) {
+  extern __shared__ __align__(16) float red[];  // [kWaves][d]
+  const int wave = threadIdx.x >> 6, l = threadIdx.x & 63;
+  f32x4 ag[NV], ab[NV], ax[NV], gm[NV];
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    ag[i] = 0.f; ab[i] = 0.f; ax[i] = 0.f; gm[i] = 0.f;
+    const int c = l * 4 + 256 * i;
+    if (c < d) gm[i] = bf16x4_to_f32(*reinterpret_cast<const u32x2*>(gamma + c));
+  }
+  for (int rr = wave; rr < kRowsPerBlock; rr += kWaves) {
+    const int row = blockIdx.x * kRowsPerBlock + rr;
+    if (row >= T) break;
+    const float mu = mean[row], r = rstd[row];
+    f32x4 xh[NV], dyv[NV];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = l * 4 + 256 * i;
+      if (c < d) {
+        xh[i] = (*reinterpret_cast<const f32x4*>(x + (int64_t)row * d + c) - mu) * r;
+        dyv[i] = bf16x4_to_f32(*reinterpret_cast<const u32x2*>(dy + (int64_t)row * d + c));
+        f32x4 dxh = dyv[i] * gm[i];
+        f32x4 t = dxh * xh[i];
+        s1 += (dxh.x + dxh.y) + (dxh.z + dxh.w);
+        s2 += (t.x + t.y) + (t.z + t.w);
+      }
+    }
+    const float c1 = wave_sum(s1) / (float)d, c2 = wave_sum(s2) / (float)d;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = l * 4 + 256 * i;
+      if (c < d) {
+        f32x4 dxh = dyv[i] * gm[i];
+        f32x4 o = (dxh - c1 - xh[i] * c2) * r;
+        o += *reinterpret_cast<const f32x4*>(dres + (int64_t)row * d + c);
+        *reinterpret_cast<f32x4*>(dx + (int64_t)row * d + c) = o;
+        if (dx_bf16) *reinterpret_cast<u32x2*>(dx_bf16 + (int64_t)row * d + c) = f32_to_bf16x4(o);
+        ag[i] += dyv[i] * xh[i];
+        ab[i] += dyv[i];
+        ax[i] += o;
+      }
+    }
+  }
+  // cross-wave sums, one quantity at a time
+  for (int qn = 0; qn < 3; ++qn) {
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = l * 4 + 256 * i;
+      if (c < d) *reinterpret_cast<f32x4*>(red + wave * d + c) = qn == 0 ? ag[i] : (qn == 1 ? ab[i] : ax[i]);
+    }
+    __syncthreads();
+    for (int c = threadIdx.x * 4; c < d; c += kThreads * 4) {
+      f32x4 s = *reinterpret_cast<const f32x4*>(red + c);
+#pragma unroll
+      for (int w = 1; w < kWaves; ++w) s += *reinterpret_cast<const f32x4*>(red + w * d + c);
+      *reinterpret_cast<f32x4*>(part + ((int64_t)blockIdx.x * 3 + qn) * d + c) = s;
+    }
+    __syncthreads();
+  }
+}
+
+// Column sums of a bf16 [T, N] matrix, first step: part[chunk][N], chunk = 128 rows.
+constexpr int kColRows = 128;
+__global__ __launch_bounds__(kThreads) void colsum_bf16_kernel(const uint16_t* __restrict__ a, int64_t lda,
+                                                               int T, int N, float* __restrict__ part) {
+  __shared__ float red[8][256 + 4];
+  const int cg = threadIdx.x & 31, rl = threadIdx.x >> 5;   // 32 column groups of 8, 8 row lanes
+  const int c0 = blockIdx.x * 256 + cg * 8;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (c0 < N) {
+    const int r_end = min(T, (int)(blockIdx.y + 1) * kColRows);
+    for (int r = blockIdx.y * kColRows + rl; r < r_end; r += 8) {
+      u32x4 v = *reinterpret_cast<const u32x4*>(a + (int64_t)r * lda + c0);
+      acc[0] += __uint_as_float(v.x << 16); acc[1] += __uint_as_float(v.x & 0xFFFF0000u);
+      acc[2] += __uint_as_float(v.y << 16); acc[3] += __uint_as_float(v.y & 0xFFFF0000u);
+      acc[4] += __uint_as_float(v.z << 16); acc[5] += __uint_as_float(v.z & 0xFFFF0000u);
+      acc[6] += __uint_as_float(v.w << 16); acc[7] += __uint_as_float(v.w & 0xFFFF0000u);
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < 8; ++k) red[rl][cg * 8 + k] = acc[k];
+  __syncthreads();
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  if (c < N) {
+    float s = red[0][threadIdx.x];
+#pragma unroll
+    for (int w = 1; w < 8; ++w) s += red[w][threadIdx.x];
+    part[(int64_t)blockIdx.y * N + c] = s;
+  }
+}
+
+// out[c] = sum_r part[r * pitch + c], rows added in order by 4 row lanes then combined.
+__global__ __launch_bounds__(kThreads) void reduce_rows_kernel(const float* __restrict__ part, int R,
+                                                               int64_t pitch, int N, float* __restrict__ out) {
+  __shared__ float red[4][64];
+  const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + cl;
+  float s = 0.f;
+  if (c < N)
+    for (int r = rl; r < R; r += 4) s += part[(int64_t)r * pitch + c];
+  red[rl][cl] = s;
+  __syncthreads();
+  if (rl == 0 && c < N) out[c] = (red[0][cl] + red[1][cl]) + (red[2][cl] + red[3][cl]);
+}
+
+__global__ void bf16_to_f32_kernel(const uint16_t* __restrict__ a, float* __restrict__ o, int64_t n4) {
+  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n4) *reinterpret_cast<f32x4*>(o + 4 * i) = bf16x4_to_f32(*reinterpret_cast<const u32x2*>(a + 4 * i));
+}
+
+int nv_for(int d) { return d <= 1024 ? 4 : d <= 2048 ? 8 : d <= 4096 ? 16 : d <= 8192 ? 32 : 0; }
+
+}  // namespace
+
+rv_status rv_ln_fwd(const void* x, int x_is_bf16, float* xcopy, const uint16_t* gamma, const uint16_t* beta,
+                    uint16_t* y, float* mean, float* rstd, int T, int d, float eps, hipStream_t st) {
+  if (!x || !gamma || !beta || !y || !mean || !rstd || T < 1 || d < 4 || d % 4 || (x_is_bf16 && !xcopy))
+    return RV_E_INVAL;
+  const int nv = nv_for(d);
+  if (!nv) return RV_E_INVAL;
+  dim3 grid((T + kWaves - 1) / kWaves), blk(kThreads);
+#define RV_LN_FWD(NV)                                                                                     \
+  if (x_is_bf16)                                                                                          \
+    hipLaunchKernelGGL((ln_fwd_kernel<NV, true>), grid, blk, 0, st, x, xcopy, gamma, beta, y, mean, rstd, T, d, eps); \
+  else                                                                                                    \
+    hipLaunchKernelGGL((ln_fwd_kernel<NV, false>), grid, blk, 0, st, x, xcopy, gamma, beta, y, mean, rstd, T, d, eps);
+  switch (nv) {
+    case 4: RV_LN_FWD(4) break;
+    case 8: RV_LN_FWD(8) break;
+    case 16: RV_LN_FWD(16) break;
+    default: RV_LN_FWD(32) break;
+  }
+#undef RV_LN_FWD
+  return rv_launch_status();
+}
+
+int rv_ln_bwd_parts(int T) { return (T + kRowsPerBlock - 1) / kRowsPerBlock; }
+
+rv_status rv_ln_bwd(const uint16_t* dy, const float* x, const float* mean, const float* rstd,
+                    const uint16_t* gamma, const float* dres, float* dx, uint16_t* dx_bf16, float* part,
+                    int T, int d, hipStream_t st) {
+  if (!dy || !x || !mean || !rstd || !gamma || !dres || !dx || !part || T < 1 || d < 4 || d % 4)
+    return RV_E_INVAL;
+  const int nv = nv_for(d);
+  if (!nv || d > 4096) return RV_E_INVAL;   // LDS: 4 * d floats
+  dim3 grid(rv_ln_bwd_parts(T)), blk(kThreads);
+  const size_t smem = (size_t)kWaves * d * sizeof(float);
+#define RV_LN_BWD(NV) \
+  hipLaunchKernelGGL((ln_bwd_kernel<NV>), grid, blk, smem, st, dy, x, mean, rstd, gamma, dres, dx, dx_bf16, part, T, d);
+  switch (nv) {
+    case 4: RV_LN_BWD(4) break;
+    case 8: RV_LN_BWD(8) break;
+    default: RV_LN_BWD(16) break;
+  }
+#undef RV_LN_BWD
+  return rv_launch_status();
+}
+
+int rv_colsum_parts(int T) { return (T + kColRows - 1) / kColRows; }
+
+rv_status rv_colsum_bf16(const uint16_t* a, int64_t lda, int T, int N, float* part, hipStream_t st) {
+  if (!a || !part || T < 1 || N < 8 || N % 8 || lda % 8) return RV_E_INVAL;
+  dim3 grid((N + 255) / 256, rv_colsum_parts(T));
+  hipLaunchKernelGGL(colsum_bf16_kernel, grid, dim3(kThreads), 0, st, a, lda, T, N, part);
+  return rv_launch_status();
+}
+
+rv_status rv_reduce_rows(const float* part, int R, int64_t pitch, int N, float* out, hipStream_t st) {
+  if (!part || !out || R < 1 || N < 1) return RV_E_INVAL;
+  hipLaunchKernelGGL(reduce_rows_kernel, dim3((N + 63) / 64), dim3(kThreads), 0, st, part, R, pitch, N, out);
+  return rv_launch_status();
+}
+
+rv_status rv_bf16_to_f32(const uint16_t* a, float* o, int64_t n, hipStream_t st) {
+  if (!a || !o || n < 4 || n % 4) return RV_E_INVAL;
+  const int64_t n4 = n / 4;
+  hipLaunchKernelGGL(bf16_to_f32_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, a, o, n4);
+  return rv_launch_status();
+}
+
+extern "C" rv_status rv_k_layernorm_fwd(const void* x, int x_is_bf16, float* xcopy, const void* gamma,
+                                        const void* beta, void* y, float* mean, float* rstd, int T, int d,
+                                        float eps, void* stream) {
+  return rv_ln_fwd(x, x_is_bf16, xcopy, (const uint16_t*)gamma, (const uint16_t*)beta, (uint16_t*)y, mean, rstd,
+                   T, d, eps, (hipStream_t)stream);
+}
+
+extern "C" rv_status rv_k_layernorm_bwd(const void* dy, const float* x, const float* mean, const float* rstd,
+                                        const void* gamma, const float* dres, float* dx, void* dx_bf16,
+                                        float* part, float* dgamma, float* dbeta, float* dbias, int T, int d,
+                                        void* stream) {
+  hipStream_t st = (hipStream_t)stream;
+  RV_TRY(rv_ln_bwd((const uint16_t*)dy, x, mean, rstd, (const uint16_t*)gamma, dres, dx, (uint16_t*)dx_bf16,
+                   part, T, d, st));
+  const int R = rv_ln_bwd_parts(T);
+  if (dgamma) RV_TRY(rv_reduce_rows(part, R, 3 * (int64_t)d, d, dgamma, st));
+  if (dbeta) RV_TRY(rv_reduce_rows(part + d, R, 3 * (int64_t)d, d, dbeta, st));
+  if (dbias) RV_TRY(rv_reduce_rows(part + 2 * d, R, 3 * (int64_t)d, d, dbias, st));
+  return RV_OK;
+}
+
+extern "C" rv_status rv_k_colsum_bf16(const void* a, int64_t lda, int T, int N, float* part, float* out,
+                                      void* stream) {
+  hipStream_t st = (hipStream_t)stream;
+  RV_TRY(rv_colsum_bf16((const uint16_t*)a, lda, T, N, part, st));
+  return rv_reduce_rows(part, rv_colsum_parts(T), N, N, out, st);
+}

@@ -17,3 +17,48 @@ def gemm_bf16(A, a_kmajor, B, b_kmajor, M, N, K, epilogue, out, out2=None, bias=
                                      resid.stride(0) if resid is not None else 0, _ptr(zin), tile,
                                      _stream_handle(stream)))
     return out
+
+
+def layernorm_fwd(x, gamma, beta, eps, xcopy=None, stream=None):
+    T, d = x.shape
+    y = torch.empty(T, d, dtype=torch.bfloat16, device="cuda")
+    mean = torch.empty(T, dtype=torch.float32, device="cuda"); rstd = torch.empty_like(mean)
+    _check(_lib.lib().rv_k_layernorm_fwd(_ptr(x), 1 if x.dtype == torch.bfloat16 else 0, _ptr(xcopy), _ptr(gamma),
+                                         _ptr(beta), _ptr(y), _ptr(mean), _ptr(rstd), T, d, eps,
+                                         _stream_handle(stream)))
+    return y, mean, rstd
+
+
+def layernorm_bwd(dy, x, mean, rstd, gamma, dres, want_bf16=True, stream=None):
+    T, d = x.shape
+    dx = torch.empty(T, d, dtype=torch.float32, device="cuda")
+    dx16 = torch.empty(T, d, dtype=torch.bfloat16, device="cuda") if want_bf16 else None
+    part = torch.empty(((T + 15) // 16) * 3 * d, dtype=torch.float32, device="cuda")
+    dg, db, dbias = (torch.empty(d, dtype=torch.float32, device="cuda") for _ in range(3))
+    _check(_lib.lib().rv_k_layernorm_bwd(_ptr(dy), _ptr(x), _ptr(mean), _ptr(rstd), _ptr(gamma), _ptr(dres),
+                                         _ptr(dx), _ptr(dx16), _ptr(part), _ptr(dg), _ptr(db), _ptr(dbias), T, d,
+                                         _stream_handle(stream)))
+    return dx, dx16, dg, db, dbias
+
+
+def colsum_bf16(a, stream=None):
+    T, N = a.shape
+    part = torch.empty(((T + 127) // 128) * N, dtype=torch.float32, device="cuda")
+    out = torch.empty(N, dtype=torch.float32, device="cuda")
+    _check(_lib.lib().rv_k_colsum_bf16(_ptr(a), a.stride(0), T, N, _ptr(part), _ptr(out), _stream_handle(stream)))
+    return out
+
+
+def attention_fwd(qkv, mb, S, d, H, stream=None):
+    out = torch.empty(mb * S, d, dtype=torch.bfloat16, device="cuda")
+    lse2 = torch.empty(mb * H * S, dtype=torch.float32, device="cuda")
+    _check(_lib.lib().rv_k_attention_fwd(_ptr(qkv), _ptr(out), _ptr(lse2), mb, S, d, H, _stream_handle(stream)))
+    return out, lse2
+
+
+def attention_bwd(qkv, out, dout, lse2, mb, S, d, H, stream=None):
+    dqkv = torch.full((mb * S, 3 * d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    scratch = torch.empty(mb * H * S, dtype=torch.float32, device="cuda")
+    _check(_lib.lib().rv_k_attention_bwd(_ptr(qkv), _ptr(out), _ptr(dout), _ptr(lse2), _ptr(scratch), _ptr(dqkv),
+                                         mb, S, d, H, _stream_handle(stream)))
+    return dqkv

@@ -56,7 +56,7 @@ def test_two_stage_chain_config1():
             gg = host64(g_st[1].last_grad())
             assert rel_l2(gg, o_st[1].last_grad) < 2e-5
             w_new = host64(g_st[1].get_params())
-            assert np.all(np.abs(w_new - (w_old - np.float64(np.float32(eta)) * gg)) <= 1e-6 * np.maximum(np.abs(w_old), 1e-30))
+            assert np.all(np.abs(w_new - (w_old - np.float64(np.float32(eta)) * gg)) <= 1e-6 * (np.abs(w_old) + eta * np.abs(gg)))
             pending[t] = (dh_g, dh_o)
         j = t - 1
         if j >= 0:
