@@ -198,6 +198,13 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint16_t* __restri
   store_tile<AKM, BM>(sa, smem);
   store_tile<BKM, BN>(sb, smem + A_BYTES);
   __syncthreads();
+  // fragments are double buffered: the LDS reads of k-step kk+1 are in flight while the
+  // MFMAs of k-step kk issue
+  bf16x8 fa[2][TM], fb[2][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) fa[0][i] = read_frag<AKM, BM>(smem, wm0 + i * 32, 0);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) fb[0][j] = read_frag<BKM, BN>(smem + A_BYTES, wn0 + j * 32, 0);
   for (int it = 0; it < nk; ++it) {
     const int cur = it & 1;
     const char* curA = smem + cur * BUF;
@@ -208,22 +215,41 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint16_t* __restri
     }
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 fa[TM], fb[TN];
+      if (kk + 1 < BK / 16) {
 #pragma unroll
-      for (int i = 0; i < TM; ++i) fa[i] = read_frag<AKM, BM>(curA, wm0 + i * 32, kk);
+        for (int i = 0; i < TM; ++i) fa[(kk + 1) & 1][i] = read_frag<AKM, BM>(curA, wm0 + i * 32, kk + 1);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) fb[j] = read_frag<BKM, BN>(curB, wn0 + j * 32, kk);
+        for (int j = 0; j < TN; ++j) fb[(kk + 1) & 1][j] = read_frag<BKM, BN>(curB, wn0 + j * 32, kk + 1);
+      }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk & 1][j], fa[kk & 1][i], acc[i][j], 0, 0, 0);
+      if (kk + 1 < BK / 16) {
+        // interleave: one LDS read group, then a share of the MFMAs
+        constexpr int NREAD = (AKM ? 2 : 1) * TM + (BKM ? 2 : 1) * TN;
+        constexpr int NMFMA = TM * TN;
+        constexpr int PER = NMFMA / NREAD > 0 ? NMFMA / NREAD : 1;
+#pragma unroll
+        for (int g = 0; g < NREAD; ++g) {
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one DS read
+          __builtin_amdgcn_sched_group_barrier(0x008, PER, 0); // PER MFMAs
+        }
+      }
     }
     if (it + 1 < nk) {
       store_tile<AKM, BM>(sa, smem + (cur ^ 1) * BUF);
       store_tile<BKM, BN>(sb, smem + (cur ^ 1) * BUF + A_BYTES);
     }
     __syncthreads();
+    if (it + 1 < nk) {
+      const char* nA = smem + (cur ^ 1) * BUF;
+#pragma unroll
+      for (int i = 0; i < TM; ++i) fa[0][i] = read_frag<AKM, BM>(nA, wm0 + i * 32, 0);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) fb[0][j] = read_frag<BKM, BN>(nA + A_BYTES, wn0 + j * 32, 0);
+    }
   }
 
   // lane holds row m = l%32 of the wave tile and, per group rg of 4 registers,
