@@ -183,9 +183,11 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
     RV_TRY(rv_ln_bwd(dtmp, x1, (const float*)(sb + p.s_m2), (const float*)(sb + p.s_r2), w + p.ln2g, dres, dres,
                      dres16_buf, part, T, d, st));
     dres16 = dres16_buf;
-    RV_TRY(rv_reduce_rows(part, ln_parts, 3 * (int64_t)d, d, gl + p.ln2g, st));
-    RV_TRY(rv_reduce_rows(part + d, ln_parts, 3 * (int64_t)d, d, gl + p.ln2b, st));
-    RV_TRY(rv_reduce_rows(part + 2 * d, ln_parts, 3 * (int64_t)d, d, gl + p.bo, st));               // dbo = sum dx1
+    {
+      const float* src[3] = {part, part + d, part + 2 * d};
+      float* dst[3] = {gl + p.ln2g, gl + p.ln2b, gl + p.bo};                                         // dbo = sum dx1
+      RV_TRY(rv_reduce_rows_multi(src, dst, 3, ln_parts, 3 * (int64_t)d, d, st));
+    }
     // attention half
     RV_TRY(gemm(st, a, d, 1, dres16, d, 1, d, d, T, RV_EPI_F32, gl + p.wo, d));                      // dWo = a^T dx1
     RV_TRY(gemm(st, dres16, d, 0, w + p.wo, d, 0, T, d, d, RV_EPI_BF16, dtmp, d));                   // da = dx1 Wo^T
@@ -197,10 +199,12 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
     uint16_t* dx16 = l == 0 ? (uint16_t*)grad_in : dres16_buf;
     RV_TRY(rv_ln_bwd(dtmp, x, (const float*)(sb + p.s_m1), (const float*)(sb + p.s_r1), w + p.ln1g, dres, dres, dx16,
                      part, T, d, st));
-    RV_TRY(rv_reduce_rows(part, ln_parts, 3 * (int64_t)d, d, gl + p.ln1g, st));
-    RV_TRY(rv_reduce_rows(part + d, ln_parts, 3 * (int64_t)d, d, gl + p.ln1b, st));
-    if (l > 0)  // the residual gradient leaving this block is dy of the block below: its b2 gradient
-      RV_TRY(rv_reduce_rows(part + 2 * d, ln_parts, 3 * (int64_t)d, d, s->grad + (size_t)(l - 1) * p.per_block + p.b2, st));
+    {
+      // the residual gradient leaving this block is dy of the block below: its b2 gradient
+      const float* src[3] = {part, part + d, part + 2 * d};
+      float* dst[3] = {gl + p.ln1g, gl + p.ln1b, l > 0 ? s->grad + (size_t)(l - 1) * p.per_block + p.b2 : nullptr};
+      RV_TRY(rv_reduce_rows_multi(src, dst, l > 0 ? 3 : 2, ln_parts, 3 * (int64_t)d, d, st));
+    }
   }
   return RV_OK;
 }

@@ -41,11 +41,31 @@ __host__ __device__ constexpr int tile_bytes(bool km, int rows) {
   return km ? BK * pitch_km(rows) : rows * PITCH_KC;
 }
 
+// GELU(z) = z * Phi(z) and its derivative Phi(z) + z * phi(z), with the normal CDF from the
+// rational-exponential form of erf (Abramowitz & Stegun 7.1.26, |error| < 1.5e-7): the tail
+// Q = 1 - Phi(|z|) = 0.5 * poly(t) * exp(-z^2/2), t = 1/(1 + p |z|/sqrt(2)), is computed
+// directly, so negative arguments lose no digits to cancellation.  The same exponential
+// serves phi(z).  About a dozen instructions instead of a library erf.
+__device__ __forceinline__ void phi_parts(float z, float& cdf, float& e) {
+  const float x = fabsf(z) * 0.70710678118654752f;
+  const float t = __builtin_amdgcn_rcpf(__fmaf_rn(0.3275911f, x, 1.0f));
+  e = __expf(-x * x);
+  float p = __fmaf_rn(1.061405429f, t, -1.453152027f);
+  p = __fmaf_rn(p, t, 1.421413741f);
+  p = __fmaf_rn(p, t, -0.284496736f);
+  p = __fmaf_rn(p, t, 0.254829592f);
+  const float q = 0.5f * p * t * e;          // upper tail of |z|
+  cdf = z < 0.f ? q : 1.0f - q;
+}
 __device__ __forceinline__ float gelu_f(float z) {
-  return 0.5f * z * (1.0f + erff(z * 0.70710678118654752f));
+  float c, e;
+  phi_parts(z, c, e);
+  return z * c;
 }
 __device__ __forceinline__ float dgelu_f(float z) {
-  return 0.5f * (1.0f + erff(z * 0.70710678118654752f)) + z * 0.3989422804014327f * __expf(-0.5f * z * z);
+  float c, e;
+  phi_parts(z, c, e);
+  return __fmaf_rn(z * 0.3989422804014327f, e, c);
 }
 
 // ---- global -> registers ---------------------------------------------------------------

@@ -35,6 +35,8 @@ rv_status rv_ln_bwd(const uint16_t* dy, const float* x, const float* mean, const
 int rv_colsum_parts(int T);   // partial rows written by rv_colsum_bf16 (each N floats)
 rv_status rv_colsum_bf16(const uint16_t* a, int64_t lda, int T, int N, float* part, hipStream_t st);
 rv_status rv_reduce_rows(const float* part, int R, int64_t pitch, int N, float* out, hipStream_t st);
+rv_status rv_reduce_rows_multi(const float* const* src, float* const* out, int njobs, int R, int64_t pitch,
+                               int N, hipStream_t st);
 rv_status rv_bf16_to_f32(const uint16_t* a, float* o, int64_t n, hipStream_t st);
 
 // ---- attention.hip ----------------------------------------------------------------

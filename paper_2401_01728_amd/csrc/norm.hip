@@ -195,18 +195,37 @@ __global__ __launch_bounds__(kThreads) void colsum_bf16_kernel(const uint16_t* _
   }
 }
 
-// out[c] = sum_r part[r * pitch + c], rows added in order by 4 row lanes then combined.
-__global__ __launch_bounds__(kThreads) void reduce_rows_kernel(const float* __restrict__ part, int R,
-                                                               int64_t pitch, int N, float* __restrict__ out) {
-  __shared__ float red[4][64];
-  const int cl = threadIdx.x & 63, rl = threadIdx.x >> 6;
-  const int c = blockIdx.x * 64 + cl;
-  float s = 0.f;
-  if (c < N)
-    for (int r = rl; r < R; r += 4) s += part[(int64_t)r * pitch + c];
-  red[rl][cl] = s;
+// out_k[c] = sum_r src_k[r * pitch + c] for up to four (src, out) pairs in one launch
+// (blockIdx.y picks the pair).  32 columns x 8 row lanes per workgroup; every row lane adds
+// its rows in order, the eight partial sums are combined in a fixed order.
+struct ReduceJobs {
+  const float* src[4];
+  float* out[4];
+};
+__global__ __launch_bounds__(kThreads) void reduce_rows_kernel(ReduceJobs jobs, int R, int64_t pitch, int N) {
+  __shared__ float red[8][33];
+  const float* __restrict__ src = jobs.src[blockIdx.y];
+  const int cl = threadIdx.x & 31, rl = threadIdx.x >> 5;
+  const int c = blockIdx.x * 32 + cl;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  if (c < N) {
+    int r = rl;
+    for (; r + 24 < R; r += 32) {
+      s0 += src[(int64_t)r * pitch + c];
+      s1 += src[(int64_t)(r + 8) * pitch + c];
+      s2 += src[(int64_t)(r + 16) * pitch + c];
+      s3 += src[(int64_t)(r + 24) * pitch + c];
+    }
+    for (; r < R; r += 8) s0 += src[(int64_t)r * pitch + c];
+  }
+  red[rl][cl] = (s0 + s1) + (s2 + s3);
   __syncthreads();
-  if (rl == 0 && c < N) out[c] = (red[0][cl] + red[1][cl]) + (red[2][cl] + red[3][cl]);
+  if (rl == 0 && c < N) {
+    float t = red[0][cl];
+#pragma unroll
+    for (int w = 1; w < 8; ++w) t += red[w][cl];
+    jobs.out[blockIdx.y][c] = t;
+  }
 }
 
 __global__ void bf16_to_f32_kernel(const uint16_t* __restrict__ a, float* __restrict__ o, int64_t n4) {
@@ -271,10 +290,21 @@ rv_status rv_colsum_bf16(const uint16_t* a, int64_t lda, int T, int N, float* pa
   return rv_launch_status();
 }
 
-rv_status rv_reduce_rows(const float* part, int R, int64_t pitch, int N, float* out, hipStream_t st) {
-  if (!part || !out || R < 1 || N < 1) return RV_E_INVAL;
-  hipLaunchKernelGGL(reduce_rows_kernel, dim3((N + 63) / 64), dim3(kThreads), 0, st, part, R, pitch, N, out);
+rv_status rv_reduce_rows_multi(const float* const* src, float* const* out, int njobs, int R, int64_t pitch,
+                               int N, hipStream_t st) {
+  if (njobs < 1 || njobs > 4 || R < 1 || N < 1) return RV_E_INVAL;
+  ReduceJobs j;
+  for (int k = 0; k < 4; ++k) {
+    j.src[k] = k < njobs ? src[k] : nullptr;
+    j.out[k] = k < njobs ? out[k] : nullptr;
+    if (k < njobs && (!src[k] || !out[k])) return RV_E_INVAL;
+  }
+  hipLaunchKernelGGL(reduce_rows_kernel, dim3((N + 31) / 32, njobs), dim3(kThreads), 0, st, j, R, pitch, N);
   return rv_launch_status();
+}
+
+rv_status rv_reduce_rows(const float* part, int R, int64_t pitch, int N, float* out, hipStream_t st) {
+  return rv_reduce_rows_multi(&part, &out, 1, R, pitch, N, st);
 }
 
 rv_status rv_bf16_to_f32(const uint16_t* a, float* o, int64_t n, hipStream_t st) {
@@ -299,10 +329,11 @@ extern "C" rv_status rv_k_layernorm_bwd(const void* dy, const float* x, const fl
   RV_TRY(rv_ln_bwd((const uint16_t*)dy, x, mean, rstd, (const uint16_t*)gamma, dres, dx, (uint16_t*)dx_bf16,
                    part, T, d, st));
   const int R = rv_ln_bwd_parts(T);
-  if (dgamma) RV_TRY(rv_reduce_rows(part, R, 3 * (int64_t)d, d, dgamma, st));
-  if (dbeta) RV_TRY(rv_reduce_rows(part + d, R, 3 * (int64_t)d, d, dbeta, st));
-  if (dbias) RV_TRY(rv_reduce_rows(part + 2 * d, R, 3 * (int64_t)d, d, dbias, st));
-  return RV_OK;
+  const float* src[3]; float* out[3]; int n = 0;
+  if (dgamma) { src[n] = part; out[n++] = dgamma; }
+  if (dbeta) { src[n] = part + d; out[n++] = dbeta; }
+  if (dbias) { src[n] = part + 2 * d; out[n++] = dbias; }
+  return n ? rv_reduce_rows_multi(src, out, n, R, 3 * (int64_t)d, d, st) : RV_OK;
 }
 
 extern "C" rv_status rv_k_colsum_bf16(const void* a, int64_t lda, int T, int N, float* part, float* out,
