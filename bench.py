@@ -141,8 +141,7 @@ def bench_stage(args, name):
 
     def step():
         t = state["t"]
-        st.forward(t, xs[t % n_in], out)
-        st.backward(t - tau, gs[(t - tau) % n_in], gin)
+        st.step(t, xs[t % n_in], t - tau, gs[(t - tau) % n_in], out, gin)
         state["t"] = t + 1
 
     ms, wall_ms = events_ms(step, args.steps, args.warmup)

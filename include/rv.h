@@ -124,6 +124,21 @@ rv_status rv_stage_forward(rv_stage* s, int64_t mb_id, const void* in, void* out
 rv_status rv_stage_backward(rv_stage* s, int64_t mb_id, const void* grad_out, void* grad_in);
 
 /*
+ * One steady-state stage step: rv_stage_forward(fwd_mb, in, out) and
+ * rv_stage_backward(bwd_mb, grad_out, grad_in) issued together, with the same result as
+ * calling them in that order: the forward runs at the parameters in force BEFORE this
+ * step's update (it does not wait for the gradient of bwd_mb - the zero-bubble property
+ * of section 3.1), the backward at the version stashed for bwd_mb, then the update of
+ * Eq. 2.  The two halves are independent and are enqueued on two streams (the stage's
+ * stream and an internal one, forked and joined with events), so their kernels overlap on
+ * the GPU; all work is ordered after what was on the stage's stream at the call and before
+ * what is enqueued on it afterwards.  With fwd_mb == bwd_mb (tau = 0) the halves run in
+ * sequence.  Errors as for the two calls; RV_E_STASH_FULL if no slot is free for fwd_mb.
+ */
+rv_status rv_stage_step(rv_stage* s, int64_t fwd_mb, const void* in, void* out, int64_t bwd_mb,
+                        const void* grad_out, void* grad_in);
+
+/*
  * The update of Eq. 2 on a bare vector: w[i] <- w[i] - eta * g[i] (one fused
  * multiply-add in fp32), optionally also emitting the bf16 rounding of the new
  * w into bf16_out (device [n] of 16-bit words, may be NULL).  All device.

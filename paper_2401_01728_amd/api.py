@@ -126,6 +126,22 @@ class Stage:
         return grad_in
 
 
+def _stage_step(self, fwd_mb, x, bwd_mb, grad_out, out=None, grad_in=None):
+    """rv_stage_step: forward(fwd_mb) beside backward(bwd_mb), then the update."""
+    if out is None:
+        out = torch.empty(self.out_shape, dtype=self.act_dtype, device="cuda")
+    if grad_in is None:
+        grad_in = torch.empty(self.in_shape, dtype=self.act_dtype, device="cuda")
+    _check(_lib.lib().rv_stage_step(self._h, fwd_mb, _ptr(self._act(x, self.in_shape)),
+                                    _ptr(self._act(out, self.out_shape)), bwd_mb,
+                                    _ptr(self._act(grad_out, self.out_shape)),
+                                    _ptr(self._act(grad_in, self.in_shape))))
+    return out, grad_in
+
+
+Stage.step = _stage_step
+
+
 def block_update(w, g, eta, bf16_out=None, stream=None):
     """rv_block_update: w <- w - eta*g in place (fp32), optional bf16 copy."""
     _dev_f32(w); _dev_f32(g, w.numel())

@@ -57,7 +57,9 @@ struct rv_stage {
   int kind = 0, dtype = 0, n_layers = 0, microbatch = 0, tau = 0;
   float eta = 0.f, ln_eps = 1e-5f;
   std::vector<int64_t> dims;
-  hipStream_t st = nullptr;
+  hipStream_t st = nullptr;   // stream the next kernel is enqueued on (the caller's, or aux inside a step)
+  hipStream_t aux = nullptr;  // second stream for the backward half of rv_stage_step
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   size_t P = 0;
   float* master = nullptr;  // [P] fp32
   float* grad = nullptr;    // [P] fp32, gradient of the last backward

@@ -22,6 +22,9 @@ int copy_kind(const rv_stage* s) { return s->dtype == RV_BF16 ? 1 : 2; }
 void free_all(rv_stage* s) {
   if (!s) return;
   if (s->kind == RV_MLP) rv_mlp_free(s); else rv_dec_free(s);
+  if (s->ev_fork) (void)hipEventDestroy(s->ev_fork);
+  if (s->ev_join) (void)hipEventDestroy(s->ev_join);
+  if (s->aux) (void)hipStreamDestroy(s->aux);
   if (s->master) (void)hipFree(s->master);
   if (s->grad) (void)hipFree(s->grad);
   for (char* v : s->ver) if (v) (void)hipFree(v);
@@ -69,6 +72,11 @@ extern "C" rv_status rv_stage_create(const rv_stage_desc* d, rv_stage** out) {
       hipMemsetAsync(s->ver[0], 0, s->P * s->ver_elem, s->st) != hipSuccess) {
     free_all(s); return RV_E_DEVICE;
   }
+  if (hipStreamCreateWithFlags(&s->aux, hipStreamNonBlocking) != hipSuccess ||
+      hipEventCreateWithFlags(&s->ev_fork, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&s->ev_join, hipEventDisableTiming) != hipSuccess) {
+    free_all(s); return RV_E_DEVICE;
+  }
   s->cur = 0;
   *out = s;
   return RV_OK;
@@ -77,6 +85,7 @@ extern "C" rv_status rv_stage_create(const rv_stage_desc* d, rv_stage** out) {
 extern "C" rv_status rv_stage_destroy(rv_stage* s) {
   if (!s) return RV_E_INVAL;
   (void)hipStreamSynchronize(s->st);
+  if (s->aux) (void)hipStreamSynchronize(s->aux);
   free_all(s);
   return RV_OK;
 }
@@ -109,9 +118,10 @@ extern "C" rv_status rv_stage_last_grad(const rv_stage* s, float* flat_out, size
   return RV_OK;
 }
 
-extern "C" rv_status rv_stage_forward(rv_stage* s, int64_t mb_id, const void* in, void* out) {
-  if (!s || !in || !out) return RV_E_INVAL;
-  if (find_slot(s, mb_id) >= 0) return RV_E_DUP_MB;
+namespace {
+
+// forward branch: bind to a free slot and the newest version, enqueue on s->st
+rv_status do_forward(rv_stage* s, int64_t mb_id, const void* in, void* out) {
   int free_i = -1;
   for (size_t i = 0; i < s->slots.size(); ++i)
     if (!s->slots[i].live) { free_i = (int)i; break; }
@@ -125,11 +135,10 @@ extern "C" rv_status rv_stage_forward(rv_stage* s, int64_t mb_id, const void* in
   return RV_OK;
 }
 
-extern "C" rv_status rv_stage_backward(rv_stage* s, int64_t mb_id, const void* grad_out, void* grad_in) {
-  if (!s || !grad_out) return RV_E_INVAL;
-  int i = find_slot(s, mb_id);
-  if (i < 0) return RV_E_UNKNOWN_MB;
-  rv_slot& sl = s->slots[i];
+// backward branch + update, enqueued on s->st.  never_in_place: the update must not
+// overwrite the current version (a forward may be reading it on another stream).
+rv_status do_backward(rv_stage* s, int slot_i, const void* grad_out, void* grad_in, bool never_in_place) {
+  rv_slot& sl = s->slots[slot_i];
   rv_status rc = s->kind == RV_MLP ? rv_mlp_backward(s, sl, grad_out, grad_in)
                                    : rv_dec_backward(s, sl, grad_out, grad_in);
   if (rc != RV_OK) return rc;
@@ -140,14 +149,58 @@ extern "C" rv_status rv_stage_backward(rv_stage* s, int64_t mb_id, const void* g
   s->ver_ref[sl.ver] -= 1;
   sl.ver = -1;
   int dst = -1;
-  if (s->ver_ref[s->cur] == 0) dst = s->cur;
+  if (!never_in_place && s->ver_ref[s->cur] == 0) dst = s->cur;
   for (size_t v = 0; dst < 0 && v < s->ver.size(); ++v)
-    if (s->ver_ref[v] == 0) dst = (int)v;
+    if (s->ver_ref[v] == 0 && !(never_in_place && (int)v == s->cur)) dst = (int)v;
   if (dst < 0) return RV_E_DEVICE;  // unreachable by the counting argument above
   rc = rv_launch_update(s->master, s->grad, s->P, s->eta, s->ver[dst], copy_kind(s), s->st);
   if (rc != RV_OK) return rc;
   s->cur = dst;
   return RV_OK;
+}
+
+}  // namespace
+
+extern "C" rv_status rv_stage_forward(rv_stage* s, int64_t mb_id, const void* in, void* out) {
+  if (!s || !in || !out) return RV_E_INVAL;
+  if (find_slot(s, mb_id) >= 0) return RV_E_DUP_MB;
+  return do_forward(s, mb_id, in, out);
+}
+
+extern "C" rv_status rv_stage_backward(rv_stage* s, int64_t mb_id, const void* grad_out, void* grad_in) {
+  if (!s || !grad_out) return RV_E_INVAL;
+  int i = find_slot(s, mb_id);
+  if (i < 0) return RV_E_UNKNOWN_MB;
+  return do_backward(s, i, grad_out, grad_in, false);
+}
+
+extern "C" rv_status rv_stage_step(rv_stage* s, int64_t fwd_mb, const void* in, void* out, int64_t bwd_mb,
+                                   const void* grad_out, void* grad_in) {
+  if (!s || !in || !out || !grad_out) return RV_E_INVAL;
+  if (find_slot(s, fwd_mb) >= 0) return RV_E_DUP_MB;
+  if (fwd_mb == bwd_mb) {  // tau = 0: the backward needs this very forward; nothing to overlap
+    RV_TRY(do_forward(s, fwd_mb, in, out));
+    return do_backward(s, find_slot(s, bwd_mb), grad_out, grad_in, false);
+  }
+  const int bi = find_slot(s, bwd_mb);
+  if (bi < 0) return RV_E_UNKNOWN_MB;
+  if (rv_stage_in_flight(s) > s->tau) return RV_E_STASH_FULL;   // no free slot for the forward
+  // fork: the backward of the old microbatch runs on the auxiliary stream beside the
+  // forward of the new one; both see the weights as they are before this step's update.
+  hipStream_t main_st = s->st;
+  RV_HIP_TRY(hipEventRecord(s->ev_fork, main_st));
+  RV_HIP_TRY(hipStreamWaitEvent(s->aux, s->ev_fork, 0));
+  rv_status rc = do_forward(s, fwd_mb, in, out);
+  if (rc == RV_OK) {
+    s->st = s->aux;
+    rc = do_backward(s, bi, grad_out, grad_in, true);
+    s->st = main_st;
+  }
+  // join even after a failure so the caller's stream stays ordered behind the aux work
+  hipError_t e1 = hipEventRecord(s->ev_join, s->aux);
+  hipError_t e2 = hipStreamWaitEvent(main_st, s->ev_join, 0);
+  if (rc != RV_OK) return rc;
+  return (e1 == hipSuccess && e2 == hipSuccess) ? RV_OK : RV_E_DEVICE;
 }
 
 extern "C" const char* rv_strerror(rv_status st) {

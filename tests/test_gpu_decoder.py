@@ -40,7 +40,7 @@ def check_tensors(got_flat, ref_flat, shapes, tol=TOL, what=""):
         assert np.abs(got[name] - ref[name]).max() <= tol * 4 * np.abs(ref[name]).max(), (what, name)
 
 
-def run_schedule(L, d, H, f, S, mb, tau, n_mb, seed, eta=1e-3, grad_std=1e-3, oracle_steps=None):
+def run_schedule(L, d, H, f, S, mb, tau, n_mb, seed, eta=1e-3, grad_std=1e-3, fused_step=False):
     import paper_2401_01728_amd as rv
     shapes = blocks.decoder_param_shapes(L, d, f)
     w0 = decoder_params_host(seed, L, d, f)
@@ -50,16 +50,25 @@ def run_schedule(L, d, H, f, S, mb, tau, n_mb, seed, eta=1e-3, grad_std=1e-3, or
     o = ostage.Stage("decoder", tau, eta, w0, n_blocks=L, d=d, h=H, f=f)
     outs = {}
     for t in range(n_mb + tau):
+        j = t - tau
+        both = fused_step and t < n_mb and j >= 0
         if t < n_mb:
             x, x64 = bf16_normal(seed, 1000 + t, (mb, S, d))
-            y = g.forward(t, x); yo = o.forward(t, x64)
-            e = rel_l2(host64(y), yo)
-            assert e < TOL, ("out", t, e)
-        j = t - tau
         if j >= 0:
             dy, dy64 = bf16_normal(seed, 2000 + j, (mb, S, d), std=grad_std)
             w_old = host64(g.get_params())
-            dx = g.backward(j, dy); dxo = o.backward(j, dy64)
+        if both:                        # rv_stage_step: the two halves overlap on two streams
+            y, dx = g.step(t, x, j, dy)
+        if t < n_mb:
+            if not both:
+                y = g.forward(t, x)
+            yo = o.forward(t, x64)
+            e = rel_l2(host64(y), yo)
+            assert e < TOL, ("out", t, e)
+        if j >= 0:
+            if not both:
+                dx = g.backward(j, dy)
+            dxo = o.backward(j, dy64)
             assert o.last_staleness == min(j, tau)
             e = rel_l2(host64(dx), dxo)
             assert e < TOL, ("grad_in", j, e)
@@ -82,10 +91,42 @@ def test_small_stage_schedules(L, d, H, f, S, mb, tau):
     run_schedule(L, d, H, f, S, mb, tau, n_mb=2 * tau + 2, seed=20 + L)
 
 
+@pytest.mark.parametrize("L,d,H,f,S,mb,tau", [(2, 128, 2, 256, 128, 2, 2), (2, 256, 2, 512, 128, 1, 0),
+                                               (3, 192, 3, 320, 64, 3, 1)])
+def test_fused_step_equals_forward_then_backward(L, d, H, f, S, mb, tau):
+    """rv_stage_step must give what forward(t); backward(t - tau) gives (oracle order F, B)."""
+    run_schedule(L, d, H, f, S, mb, tau, n_mb=2 * tau + 4, seed=40 + L, fused_step=True)
+
+
+def test_fused_step_is_bitwise_the_two_calls():
+    import paper_2401_01728_amd as rv
+    L, d, H, f, S, mb, tau = 2, 128, 2, 256, 128, 2, 2
+    w0 = dev(decoder_params_host(9, L, d, f))
+    res = []
+    for fused in (False, True):
+        g = rv.Stage.decoder(L, d, H, f, S, mb, tau, 1e-3); g.set_params(w0)
+        outs = []
+        for t in range(8 + tau):
+            j = t - tau
+            x, _ = bf16_normal(9, 1000 + t, (mb, S, d)); dy, _ = bf16_normal(9, 2000 + max(j, 0), (mb, S, d), std=1e-3)
+            if fused and t < 8 and j >= 0:
+                y, dx = g.step(t, x, j, dy); outs += [y, dx]
+            else:
+                if t < 8:
+                    outs.append(g.forward(t, x))
+                if j >= 0:
+                    outs.append(g.backward(j, dy))
+        outs.append(g.get_params())
+        torch.cuda.synchronize()
+        res.append([o.clone() for o in outs])
+    for a, b in zip(*res):
+        assert torch.equal(a, b)
+
+
 def test_deep_staleness_reduced_shape():
     """The 12-block, tau = 4, 25-head stage at reduced widths (d=1600/4, ffn 6400/4 keep the
     head size 64 ... here 400 is not a multiple of 64, so d = 448 with 7 heads)."""
-    run_schedule(12, 448, 7, 1792, 128, 2, 4, n_mb=12, seed=5)
+    run_schedule(12, 448, 7, 1792, 128, 2, 4, n_mb=12, seed=5, fused_step=True)
 
 
 def test_decoder_error_paths():
