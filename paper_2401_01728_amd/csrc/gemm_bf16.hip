@@ -10,10 +10,10 @@
 //   dW       dW = x^T dy   : A = x  k-major,      B = dy k-major      (contraction over tokens)
 //
 // Tiling: a workgroup of 256 lanes (2x2 waves) owns a BM x BN tile and walks K in steps
-// of 64.  Tiles are staged global -> registers -> LDS, double buffered, one barrier per
+// of BK (64 or 32).  Tiles are staged global -> registers -> LDS, double buffered, one barrier per
 // step.  A wave owns (BM/2) x (BN/2) as 32x32 MFMA tiles (v_mfma_f32_32x32x16_bf16).
-//   k-contiguous operands sit in LDS as [row][64 k] with a 144-byte row pitch, read as one
-//   16-byte fragment per lane;
+//   k-contiguous operands sit in LDS as [row][BK k], read as one
+//   16-byte fragment per lane (pitch BK*2+16 bytes);
 //   k-major operands sit as [64 k][cols] with pitch cols*2+64 bytes and are read with the
 //   LDS transpose read (ds_read_b64_tr_b16), which hands each lane four consecutive k of
 //   one column: no register transposes, no transposed copies of activations in HBM.
@@ -32,13 +32,13 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int BK = 64;
 constexpr int kThreads = 256;
-constexpr int PITCH_KC = BK * 2 + 16;  // bytes per row of a k-contiguous tile
 
+// LDS pitches (bytes).  k-contiguous tile: [row][BK k] + 16; k-major tile: [BK k][cols] + 64.
+__host__ __device__ constexpr int pitch_kc(int bk) { return bk * 2 + 16; }
 __host__ __device__ constexpr int pitch_km(int cols) { return cols * 2 + 64; }
-__host__ __device__ constexpr int tile_bytes(bool km, int rows) {
-  return km ? BK * pitch_km(rows) : rows * PITCH_KC;
+__host__ __device__ constexpr int tile_bytes(bool km, int rows, int bk) {
+  return km ? bk * pitch_km(rows) : rows * pitch_kc(bk);
 }
 
 // GELU(z) = z * Phi(z) and its derivative Phi(z) + z * phi(z), with the normal CDF from the
@@ -69,43 +69,56 @@ __device__ __forceinline__ float dgelu_f(float z) {
 }
 
 // ---- global -> registers ---------------------------------------------------------------
-template <bool KM, int ROWS>
+// A lane moves N 16-byte chunks of a tile per k-step.  Their element offsets (row clamped to
+// the matrix so ragged tiles read valid memory) are computed once; a k-step only adds k0.
+template <bool KM, int ROWS, int BK>
 struct Stage {
-  static constexpr int N = ROWS / 32;  // 16-byte chunks per lane
+  static constexpr int N = ROWS * BK / 8 / kThreads;
   u32x4 v[N];
+  int off[N];
 };
 
 // rows: extent of the non-contraction dimension (M or N) of this operand, r0: tile origin
-template <bool KM, int ROWS>
-__device__ __forceinline__ void load_tile(Stage<KM, ROWS>& s, const uint16_t* __restrict__ g,
-                                          int64_t ld, int r0, int rows, int k0) {
+template <bool KM, int ROWS, int BK>
+__device__ __forceinline__ void init_tile(Stage<KM, ROWS, BK>& s, int64_t ld, int r0, int rows) {
   const int t = threadIdx.x;
 #pragma unroll
-  for (int i = 0; i < Stage<KM, ROWS>::N; ++i) {
+  for (int i = 0; i < Stage<KM, ROWS, BK>::N; ++i) {
     const int idx = t + kThreads * i;
     if (!KM) {
-      int row = r0 + idx / 8, c = idx % 8;
+      constexpr int CPR = BK / 8;
+      int row = r0 + idx / CPR, c = idx % CPR;
       row = row < rows ? row : rows - 1;
-      s.v[i] = *reinterpret_cast<const u32x4*>(g + (int64_t)row * ld + k0 + c * 8);
+      s.off[i] = row * (int)ld + c * 8;
     } else {
       constexpr int CPR = ROWS / 8;
       int kr = idx / CPR, c = idx % CPR;
       int col = r0 + c * 8;
       col = col < rows ? col : rows - 8;
-      s.v[i] = *reinterpret_cast<const u32x4*>(g + (int64_t)(k0 + kr) * ld + col);
+      s.off[i] = kr * (int)ld + col;
     }
   }
 }
 
-template <bool KM, int ROWS>
-__device__ __forceinline__ void store_tile(const Stage<KM, ROWS>& s, char* lds) {
+template <bool KM, int ROWS, int BK>
+__device__ __forceinline__ void load_tile(Stage<KM, ROWS, BK>& s, const uint16_t* __restrict__ g,
+                                          int64_t ld, int k0) {
+  const uint16_t* base = KM ? g + (int64_t)k0 * ld : g + k0;
+#pragma unroll
+  for (int i = 0; i < Stage<KM, ROWS, BK>::N; ++i)
+    s.v[i] = *reinterpret_cast<const u32x4*>(base + s.off[i]);
+}
+
+template <bool KM, int ROWS, int BK>
+__device__ __forceinline__ void store_tile(const Stage<KM, ROWS, BK>& s, char* lds) {
   const int t = threadIdx.x;
 #pragma unroll
-  for (int i = 0; i < Stage<KM, ROWS>::N; ++i) {
+  for (int i = 0; i < Stage<KM, ROWS, BK>::N; ++i) {
     const int idx = t + kThreads * i;
     if (!KM) {
-      int row = idx / 8, c = idx % 8;
-      *reinterpret_cast<u32x4*>(lds + row * PITCH_KC + c * 16) = s.v[i];
+      constexpr int CPR = BK / 8;
+      int row = idx / CPR, c = idx % CPR;
+      *reinterpret_cast<u32x4*>(lds + row * pitch_kc(BK) + c * 16) = s.v[i];
     } else {
       constexpr int CPR = ROWS / 8;
       int kr = idx / CPR, c = idx % CPR;
@@ -116,11 +129,11 @@ __device__ __forceinline__ void store_tile(const Stage<KM, ROWS>& s, char* lds) 
 
 // ---- LDS -> MFMA fragment ---------------------------------------------------------------
 // Fragment of 32 rows (row index = lane % 32) x 16 k (k = 8*(lane/32) .. +7) for k-step kk.
-template <bool KM, int ROWS>
+template <bool KM, int ROWS, int BK>
 __device__ __forceinline__ bf16x8 read_frag(const char* lds, int row0, int kk) {
   const int l = threadIdx.x & 63;
   if (!KM) {
-    const char* p = lds + (row0 + (l & 31)) * PITCH_KC + kk * 32 + (l >> 5) * 16;
+    const char* p = lds + (row0 + (l & 31)) * pitch_kc(BK) + kk * 32 + (l >> 5) * 16;
     return *reinterpret_cast<const bf16x8*>(p);
   } else {
     const int q = l >> 4, i = l & 15;
@@ -187,12 +200,12 @@ __device__ __forceinline__ void epilogue4(const Epi& e, int m, int n, f32x4 a) {
   }
 }
 
-template <int BM, int BN, bool AKM, bool BKM, int EPI>
-__global__ __launch_bounds__(kThreads) void gemm_kernel(const uint16_t* __restrict__ A, int64_t lda,
-                                                        const uint16_t* __restrict__ B, int64_t ldb,
-                                                        int M, int N, int K, int tiles_m, Epi e) {
-  constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32;
-  constexpr int A_BYTES = tile_bytes(AKM, BM), B_BYTES = tile_bytes(BKM, BN);
+template <int BM, int BN, int BK, int WPE, bool AKM, bool BKM, int EPI>
+__global__ __launch_bounds__(kThreads, WPE) void gemm_kernel(const uint16_t* __restrict__ A, int64_t lda,
+                                                             const uint16_t* __restrict__ B, int64_t ldb,
+                                                             int M, int N, int K, int tiles_m, Epi e) {
+  constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32, KSTEPS = BK / 16;
+  constexpr int A_BYTES = tile_bytes(AKM, BM, BK), B_BYTES = tile_bytes(BKM, BN, BK);
   extern __shared__ __align__(16) char smem[];
   constexpr int BUF = A_BYTES + B_BYTES;   // buffer b: A tile at b*BUF, B tile behind it
 
@@ -210,44 +223,46 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint16_t* __restri
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  Stage<AKM, BM> sa;
-  Stage<BKM, BN> sb;
+  Stage<AKM, BM, BK> sa;
+  Stage<BKM, BN, BK> sb;
+  init_tile<AKM, BM, BK>(sa, lda, m0, M);
+  init_tile<BKM, BN, BK>(sb, ldb, n0, N);
   const int nk = K / BK;
-  load_tile<AKM, BM>(sa, A, lda, m0, M, 0);
-  load_tile<BKM, BN>(sb, B, ldb, n0, N, 0);
-  store_tile<AKM, BM>(sa, smem);
-  store_tile<BKM, BN>(sb, smem + A_BYTES);
+  load_tile<AKM, BM, BK>(sa, A, lda, 0);
+  load_tile<BKM, BN, BK>(sb, B, ldb, 0);
+  store_tile<AKM, BM, BK>(sa, smem);
+  store_tile<BKM, BN, BK>(sb, smem + A_BYTES);
   __syncthreads();
   // fragments are double buffered: the LDS reads of k-step kk+1 are in flight while the
   // MFMAs of k-step kk issue
   bf16x8 fa[2][TM], fb[2][TN];
 #pragma unroll
-  for (int i = 0; i < TM; ++i) fa[0][i] = read_frag<AKM, BM>(smem, wm0 + i * 32, 0);
+  for (int i = 0; i < TM; ++i) fa[0][i] = read_frag<AKM, BM, BK>(smem, wm0 + i * 32, 0);
 #pragma unroll
-  for (int j = 0; j < TN; ++j) fb[0][j] = read_frag<BKM, BN>(smem + A_BYTES, wn0 + j * 32, 0);
+  for (int j = 0; j < TN; ++j) fb[0][j] = read_frag<BKM, BN, BK>(smem + A_BYTES, wn0 + j * 32, 0);
   for (int it = 0; it < nk; ++it) {
     const int cur = it & 1;
     const char* curA = smem + cur * BUF;
     const char* curB = curA + A_BYTES;
     if (it + 1 < nk) {
-      load_tile<AKM, BM>(sa, A, lda, m0, M, (it + 1) * BK);
-      load_tile<BKM, BN>(sb, B, ldb, n0, N, (it + 1) * BK);
+      load_tile<AKM, BM, BK>(sa, A, lda, (it + 1) * BK);
+      load_tile<BKM, BN, BK>(sb, B, ldb, (it + 1) * BK);
     }
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      if (kk + 1 < BK / 16) {
+    for (int kk = 0; kk < KSTEPS; ++kk) {
+      if (kk + 1 < KSTEPS) {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) fa[(kk + 1) & 1][i] = read_frag<AKM, BM>(curA, wm0 + i * 32, kk + 1);
+        for (int i = 0; i < TM; ++i) fa[(kk + 1) & 1][i] = read_frag<AKM, BM, BK>(curA, wm0 + i * 32, kk + 1);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) fb[(kk + 1) & 1][j] = read_frag<BKM, BN>(curB, wn0 + j * 32, kk + 1);
+        for (int j = 0; j < TN; ++j) fb[(kk + 1) & 1][j] = read_frag<BKM, BN, BK>(curB, wn0 + j * 32, kk + 1);
       }
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk & 1][j], fa[kk & 1][i], acc[i][j], 0, 0, 0);
-      if (kk + 1 < BK / 16) {
-        // interleave: one LDS read group, then a share of the MFMAs
+      if (kk + 1 < KSTEPS) {
+        // interleave: one LDS read, then a share of the MFMAs
         constexpr int NREAD = (AKM ? 2 : 1) * TM + (BKM ? 2 : 1) * TN;
         constexpr int NMFMA = TM * TN;
         constexpr int PER = NMFMA / NREAD > 0 ? NMFMA / NREAD : 1;
@@ -259,16 +274,16 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint16_t* __restri
       }
     }
     if (it + 1 < nk) {
-      store_tile<AKM, BM>(sa, smem + (cur ^ 1) * BUF);
-      store_tile<BKM, BN>(sb, smem + (cur ^ 1) * BUF + A_BYTES);
+      store_tile<AKM, BM, BK>(sa, smem + (cur ^ 1) * BUF);
+      store_tile<BKM, BN, BK>(sb, smem + (cur ^ 1) * BUF + A_BYTES);
     }
     __syncthreads();
     if (it + 1 < nk) {
       const char* nA = smem + (cur ^ 1) * BUF;
 #pragma unroll
-      for (int i = 0; i < TM; ++i) fa[0][i] = read_frag<AKM, BM>(nA, wm0 + i * 32, 0);
+      for (int i = 0; i < TM; ++i) fa[0][i] = read_frag<AKM, BM, BK>(nA, wm0 + i * 32, 0);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) fb[0][j] = read_frag<BKM, BN>(nA + A_BYTES, wn0 + j * 32, 0);
+      for (int j = 0; j < TN; ++j) fb[0][j] = read_frag<BKM, BN, BK>(nA + A_BYTES, wn0 + j * 32, 0);
     }
   }
 
@@ -291,11 +306,11 @@ __global__ __launch_bounds__(kThreads) void gemm_kernel(const uint16_t* __restri
   }
 }
 
-template <int BM, int BN, bool AKM, bool BKM, int EPI>
+template <int BM, int BN, int BK, int WPE, bool AKM, bool BKM, int EPI>
 rv_status launch(const rv_gemm_args& g, hipStream_t st) {
-  constexpr int smem = 2 * (tile_bytes(AKM, BM) + tile_bytes(BKM, BN));
+  constexpr int smem = 2 * (tile_bytes(AKM, BM, BK) + tile_bytes(BKM, BN, BK));
   static bool configured = false;
-  auto kern = gemm_kernel<BM, BN, AKM, BKM, EPI>;
+  auto kern = gemm_kernel<BM, BN, BK, WPE, AKM, BKM, EPI>;
   if (!configured) {
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
       return RV_E_DEVICE;
@@ -308,22 +323,29 @@ rv_status launch(const rv_gemm_args& g, hipStream_t st) {
   return rv_launch_status();
 }
 
+// Tile choice.  256x256 (one workgroup per CU, 128x128 per wave) has the lowest LDS traffic
+// per MFMA; 128x256 (two workgroups per CU, 64x128 per wave, BK 32) overlaps one workgroup's
+// load/epilogue phases with the other's MFMAs; 128x128 fills the chip on small outputs.
 template <bool AKM, bool BKM, int EPI>
 rv_status pick_tile(const rv_gemm_args& g, hipStream_t st) {
-  // the largest tile that still gives every CU a workgroup
-  const long t256 = (long)((g.M + 255) / 256) * ((g.N + 255) / 256);
-  const long t128 = (long)((g.M + 127) / 128) * ((g.N + 127) / 128);
-  if (g.tile == 256 || (g.tile == 0 && t256 >= 200)) return launch<256, 256, AKM, BKM, EPI>(g, st);
-  (void)t128;
-  return launch<128, 128, AKM, BKM, EPI>(g, st);
+  auto tiles = [&](int bm, int bn) { return (long)((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn); };
+  int tile = g.tile;
+  if (tile == 0) tile = tiles(256, 256) >= 384 ? 256 : (tiles(128, 256) >= 384 ? 192 : 128);
+  if (tile == 256) return launch<256, 256, 64, 1, AKM, BKM, EPI>(g, st);
+  if (tile == 192) return launch<128, 256, 32, 2, AKM, BKM, EPI>(g, st);
+  if (tile == 128) return launch<128, 128, 64, 2, AKM, BKM, EPI>(g, st);
+  return RV_E_INVAL;
 }
 
 }  // namespace
 
 rv_status rv_gemm_bf16(const rv_gemm_args& g, hipStream_t st) {
-  if (!g.A || !g.B || !g.out || g.M < 8 || g.N < 8 || g.K < BK) return RV_E_INVAL;
-  if (g.K % BK || g.N % 8 || g.M % 8 || g.lda % 8 || g.ldb % 8 || g.ldo % 4) return RV_E_INVAL;
+  if (!g.A || !g.B || !g.out || g.M < 8 || g.N < 8 || g.K < 64) return RV_E_INVAL;
+  if (g.K % 64 || g.N % 8 || g.M % 8 || g.lda % 8 || g.ldb % 8 || g.ldo % 4) return RV_E_INVAL;
   if ((((uintptr_t)g.A) | ((uintptr_t)g.B) | ((uintptr_t)g.out)) & 15) return RV_E_INVAL;
+  // tile offsets are kept in 32 bits
+  if ((int64_t)(g.a_kmajor ? g.K : g.M) * g.lda >= (1ll << 31) || (int64_t)(g.b_kmajor ? g.K : g.N) * g.ldb >= (1ll << 31))
+    return RV_E_INVAL;
   const bool need_bias = g.epi == EPI_BF16_BIAS || g.epi == EPI_F32_BIAS_RESID ||
                          g.epi == EPI_BF16_BIAS_GELU || g.epi == EPI_F32_BIAS_RESID_BF16;
   if (need_bias && (!g.bias || (((uintptr_t)g.bias) & 7))) return RV_E_INVAL;
