@@ -200,6 +200,28 @@ __device__ __forceinline__ void epilogue4(const Epi& e, int m, int n, f32x4 a) {
   }
 }
 
+// lane holds row m = l%32 of the wave tile and, per group rg of 4 registers,
+// columns 8*rg + 4*(l/32) .. +3
+template <int TM, int TN, int EPI>
+__device__ __forceinline__ void write_tile(const f32x16 (&acc)[TM][TN], const Epi& e, int mw, int nw, int M, int N) {
+  const int l = threadIdx.x & 63;
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int m = mw + i * 32 + (l & 31);
+    if (m >= M) continue;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+#pragma unroll
+      for (int rg = 0; rg < 4; ++rg) {
+        const int n = nw + j * 32 + 8 * rg + 4 * (l >> 5);
+        if (n >= N) continue;
+        f32x4 a = {acc[i][j][4 * rg], acc[i][j][4 * rg + 1], acc[i][j][4 * rg + 2], acc[i][j][4 * rg + 3]};
+        epilogue4<EPI>(e, m, n, a);
+      }
+    }
+  }
+}
+
 template <int BM, int BN, int BK, int WPE, bool AKM, bool BKM, int EPI>
 __global__ __launch_bounds__(kThreads, WPE) void gemm_kernel(const uint16_t* __restrict__ A, int64_t lda,
                                                              const uint16_t* __restrict__ B, int64_t ldb,
@@ -287,23 +309,194 @@ __global__ __launch_bounds__(kThreads, WPE) void gemm_kernel(const uint16_t* __r
     }
   }
 
-  // lane holds row m = l%32 of the wave tile and, per group rg of 4 registers,
-  // columns 8*rg + 4*(l/32) .. +3
+  write_tile<TM, TN, EPI>(acc, e, m0 + wm0, n0 + wn0, M, N);
+}
+
+// ---- direct-to-LDS pipeline ---------------------------------------------------------------
+// Tiles go global -> LDS with global_load_lds_dwordx4: no staging registers, no LDS write
+// instructions.  One such instruction fills 1 KiB of LDS (lane i -> base + 16 i), so the
+// tile is unpadded and bank conflicts are removed by an XOR swizzle of the 16-byte chunk
+// index instead; because a lane's LDS slot is fixed, the swizzle is applied to the GLOBAL
+// address a lane fetches.
+//   k-contiguous tile [rows][BK]: physical chunk = c ^ ((row / rows_per_256B) % chunks_per_row)
+//   k-major tile [BK][cols]     : physical chunk = c ^ ((k & 3) << 2)   (64-byte granules)
+// NS stages form a ring: the loads of tile t+NS-1 are issued right after the barrier that
+// opens tile t, so a tile has NS-1 k-steps of compute time to arrive.
+__host__ __device__ constexpr int dtl_tile_bytes(int rows, int bk) { return rows * bk * 2; }
+
+template <bool KM, int ROWS, int BK>
+struct Dtl {
+  static constexpr int N = ROWS * BK / 8 / kThreads;   // loads per lane per tile
+  int off[N];
+};
+
+template <bool KM, int ROWS, int BK>
+__device__ __forceinline__ void dtl_init(Dtl<KM, ROWS, BK>& s, int64_t ld, int r0, int rows) {
+  const int wave = threadIdx.x >> 6, l = threadIdx.x & 63;
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const int m = m0 + wm0 + i * 32 + (l & 31);
-    if (m >= M) continue;
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-#pragma unroll
-      for (int rg = 0; rg < 4; ++rg) {
-        const int n = n0 + wn0 + j * 32 + 8 * rg + 4 * (l >> 5);
-        if (n >= N) continue;
-        f32x4 a = {acc[i][j][4 * rg], acc[i][j][4 * rg + 1], acc[i][j][4 * rg + 2], acc[i][j][4 * rg + 3]};
-        epilogue4<EPI>(e, m, n, a);
-      }
+  for (int i = 0; i < Dtl<KM, ROWS, BK>::N; ++i) {
+    const int slot = (i * 4 + wave) * 64 + l;
+    if (!KM) {
+      constexpr int CPR = BK / 8, R256 = 256 / (BK * 2);
+      const int row = slot / CPR, c = (slot % CPR) ^ ((row / R256) % CPR);
+      int gr = r0 + row;
+      gr = gr < rows ? gr : rows - 1;
+      s.off[i] = gr * (int)ld + c * 8;
+    } else {
+      constexpr int CPR = ROWS / 8;
+      const int kr = slot / CPR, c = (slot % CPR) ^ ((kr & 3) << 2);
+      int col = r0 + c * 8;
+      col = col < rows ? col : rows - 8;
+      s.off[i] = kr * (int)ld + col;
     }
   }
+}
+
+template <bool KM, int ROWS, int BK>
+__device__ __forceinline__ void dtl_issue(const Dtl<KM, ROWS, BK>& s, const uint16_t* __restrict__ g,
+                                          int64_t ld, int k0, char* lds) {
+  const uint16_t* base = KM ? g + (int64_t)k0 * ld : g + k0;
+  const int wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int i = 0; i < Dtl<KM, ROWS, BK>::N; ++i) {
+    // LDS byte address of this wave's 1 KiB block (wave-uniform, goes to M0; the hardware
+    // adds 16 * lane).  Issued as inline assembly: the compiler would otherwise make every
+    // later LDS read wait for ALL outstanding loads, which defeats the ring.  The kernel
+    // orders them itself with explicit vmcnt waits and barriers.
+    const int m0v = __builtin_amdgcn_readfirstlane((int)(size_t)lds + (i * 4 + wave) * 1024);
+    const uint16_t* src = base + s.off[i];
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                 :
+                 : "v"(src), "s"(m0v)
+                 : "memory", "m0");
+  }
+}
+
+template <bool KM, int ROWS, int BK>
+__device__ __forceinline__ bf16x8 dtl_frag(const char* lds, int row0, int kk) {
+  const int l = threadIdx.x & 63;
+  if (!KM) {
+    constexpr int CPR = BK / 8, R256 = 256 / (BK * 2);
+    const int row = row0 + (l & 31);
+    const int c = (kk * 2 + (l >> 5)) ^ ((row / R256) % CPR);
+    return *reinterpret_cast<const bf16x8*>(lds + row * (BK * 2) + c * 16);
+  } else {
+    const int q = l >> 4, i = l & 15;
+    const int kr = kk * 16 + 8 * (q >> 1) + (i >> 2);
+    const int col = row0 + 16 * (q & 1) + 4 * (i & 3);
+    const int c = (col >> 3) ^ ((kr & 3) << 2);
+    const char* p = lds + kr * (ROWS * 2) + c * 16 + (col & 7) * 2;
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+        (s16x4 __attribute__((address_space(3)))*)(p + 4 * (ROWS * 2)));
+    s16x8 r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, r);
+  }
+}
+
+// s_waitcnt vmcnt(n) only (expcnt, lgkmcnt left at "no wait"); n < 64
+#define RV_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
+
+template <int BM, int BN, int BK, int NS, int WPE, bool AKM, bool BKM, int EPI>
+__global__ __launch_bounds__(kThreads, WPE) void gemm_dtl_kernel(const uint16_t* __restrict__ A, int64_t lda,
+                                                                 const uint16_t* __restrict__ B, int64_t ldb,
+                                                                 int M, int N, int K, int tiles_m, Epi e) {
+  constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32, KSTEPS = BK / 16;
+  constexpr int A_BYTES = dtl_tile_bytes(BM, BK), B_BYTES = dtl_tile_bytes(BN, BK);
+  constexpr int BUF = A_BYTES + B_BYTES;
+  constexpr int LPT = Dtl<AKM, BM, BK>::N + Dtl<BKM, BN, BK>::N;   // loads per lane per tile
+  static_assert(LPT * (NS - 2) < 64, "vmcnt range");
+  extern __shared__ __align__(1024) char smem[];
+
+  const int bm = blockIdx.x % tiles_m, bn = blockIdx.x / tiles_m;
+  const int m0 = bm * BM, n0 = bn * BN;
+  const int wave = threadIdx.x >> 6;
+  const int wm0 = (wave & 1) * WM, wn0 = (wave >> 1) * WN;
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  Dtl<AKM, BM, BK> da;
+  Dtl<BKM, BN, BK> db;
+  dtl_init<AKM, BM, BK>(da, lda, m0, M);
+  dtl_init<BKM, BN, BK>(db, ldb, n0, N);
+  const int nk = K / BK;
+#pragma unroll
+  for (int t = 0; t < NS - 1; ++t)
+    if (t < nk) {
+      dtl_issue<AKM, BM, BK>(da, A, lda, t * BK, smem + t * BUF);
+      dtl_issue<BKM, BN, BK>(db, B, ldb, t * BK, smem + t * BUF + A_BYTES);
+    }
+  int stage = 0;               // ring slot of tile `it`
+  int fill = NS - 1;           // ring slot the next issued tile goes to
+  for (int it = 0; it < nk; ++it) {
+    // tile `it` has landed once at most the loads of the newer tiles are outstanding
+    const int newer = nk - 1 - it;
+    if (NS >= 4 && newer >= NS - 2) RV_WAIT_VMCNT(LPT * (NS - 2));
+    else if (NS >= 3 && newer >= 1) { if (NS >= 4 && newer >= 2) RV_WAIT_VMCNT(LPT * 2); else RV_WAIT_VMCNT(LPT * 1); }
+    else RV_WAIT_VMCNT(0);
+    __syncthreads();           // everyone's part of tile `it` is in LDS; everyone left tile it-1
+    if (it + NS - 1 < nk) {
+      dtl_issue<AKM, BM, BK>(da, A, lda, (it + NS - 1) * BK, smem + fill * BUF);
+      dtl_issue<BKM, BN, BK>(db, B, ldb, (it + NS - 1) * BK, smem + fill * BUF + A_BYTES);
+    }
+    const char* curA = smem + stage * BUF;
+    const char* curB = curA + A_BYTES;
+    bf16x8 fa[2][TM], fb[2][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa[0][i] = dtl_frag<AKM, BM, BK>(curA, wm0 + i * 32, 0);
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb[0][j] = dtl_frag<BKM, BN, BK>(curB, wn0 + j * 32, 0);
+#pragma unroll
+    for (int kk = 0; kk < KSTEPS; ++kk) {
+      if (kk + 1 < KSTEPS) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[(kk + 1) & 1][i] = dtl_frag<AKM, BM, BK>(curA, wm0 + i * 32, kk + 1);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[(kk + 1) & 1][j] = dtl_frag<BKM, BN, BK>(curB, wn0 + j * 32, kk + 1);
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk & 1][j], fa[kk & 1][i], acc[i][j], 0, 0, 0);
+      if (kk + 1 < KSTEPS) {
+        constexpr int NREAD = (AKM ? 2 : 1) * TM + (BKM ? 2 : 1) * TN;
+        constexpr int NMFMA = TM * TN;
+        constexpr int PER = NMFMA / NREAD > 0 ? NMFMA / NREAD : 1;
+#pragma unroll
+        for (int g = 0; g < NREAD; ++g) {
+          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);
+        }
+      }
+    }
+    stage = stage + 1 == NS ? 0 : stage + 1;
+    fill = fill + 1 == NS ? 0 : fill + 1;
+  }
+  write_tile<TM, TN, EPI>(acc, e, m0 + wm0, n0 + wn0, M, N);
+}
+
+template <int BM, int BN, int BK, int NS, int WPE, bool AKM, bool BKM, int EPI>
+rv_status launch_dtl(const rv_gemm_args& g, hipStream_t st) {
+  constexpr int smem = NS * (dtl_tile_bytes(BM, BK) + dtl_tile_bytes(BN, BK));
+  static bool configured = false;
+  auto kern = gemm_dtl_kernel<BM, BN, BK, NS, WPE, AKM, BKM, EPI>;
+  if (!configured) {
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
+      return RV_E_DEVICE;
+    configured = true;
+  }
+  const int tm = (g.M + BM - 1) / BM, tn = (g.N + BN - 1) / BN;
+  Epi e{g.out, g.ldo, g.out2, g.bias, g.resid, g.ldr, g.zin, nullptr};
+  hipLaunchKernelGGL(kern, dim3(tm * tn), dim3(kThreads), smem, st, g.A, g.lda, g.B, g.ldb, g.M, g.N, g.K,
+                     tm, e);
+  return rv_launch_status();
 }
 
 template <int BM, int BN, int BK, int WPE, bool AKM, bool BKM, int EPI>
@@ -323,17 +516,21 @@ rv_status launch(const rv_gemm_args& g, hipStream_t st) {
   return rv_launch_status();
 }
 
-// Tile choice.  256x256 (one workgroup per CU, 128x128 per wave) has the lowest LDS traffic
-// per MFMA; 128x256 (two workgroups per CU, 64x128 per wave, BK 32) overlaps one workgroup's
-// load/epilogue phases with the other's MFMAs; 128x128 fills the chip on small outputs.
+// Tile choice (codes >= 2000: direct-to-LDS ring; others: register-staged double buffer).
+// 256x256 (one workgroup per CU, 128x128 per wave) has the lowest LDS traffic per MFMA;
+// 128x256 (two workgroups per CU, 64x128 per wave) overlaps one workgroup's barrier and
+// epilogue phases with the other's MFMAs; 128x128 fills the chip on small outputs.
 template <bool AKM, bool BKM, int EPI>
 rv_status pick_tile(const rv_gemm_args& g, hipStream_t st) {
   auto tiles = [&](int bm, int bn) { return (long)((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn); };
   int tile = g.tile;
-  if (tile == 0) tile = tiles(256, 256) >= 384 ? 256 : (tiles(128, 256) >= 384 ? 192 : 128);
+  if (tile == 0) tile = tiles(256, 256) >= 512 ? 2256 : (tiles(128, 256) >= 512 ? 2192 : 2128);
   if (tile == 256) return launch<256, 256, 64, 1, AKM, BKM, EPI>(g, st);
   if (tile == 192) return launch<128, 256, 32, 2, AKM, BKM, EPI>(g, st);
   if (tile == 128) return launch<128, 128, 64, 2, AKM, BKM, EPI>(g, st);
+  if (tile == 2256) return launch_dtl<256, 256, 32, 4, 1, AKM, BKM, EPI>(g, st);
+  if (tile == 2192) return launch_dtl<128, 256, 32, 3, 2, AKM, BKM, EPI>(g, st);
+  if (tile == 2128) return launch_dtl<128, 128, 64, 2, 2, AKM, BKM, EPI>(g, st);
   return RV_E_INVAL;
 }
 
