@@ -141,7 +141,11 @@ def bench_stage(args, name):
 
     def step():
         t = state["t"]
-        st.step(t, xs[t % n_in], t - tau, gs[(t - tau) % n_in], out, gin)
+        if args.no_overlap:            # the two halves as separate calls on one stream
+            st.forward(t, xs[t % n_in], out)
+            st.backward(t - tau, gs[(t - tau) % n_in], gin)
+        else:
+            st.step(t, xs[t % n_in], t - tau, gs[(t - tau) % n_in], out, gin)
         state["t"] = t + 1
 
     ms, wall_ms = events_ms(step, args.steps, args.warmup)
@@ -193,6 +197,8 @@ def main():
     ap.add_argument("--rings", type=int, default=4)
     ap.add_argument("--n", type=float, default=None)
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="issue forward and backward as two calls on one stream (for per-kernel profiles)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)

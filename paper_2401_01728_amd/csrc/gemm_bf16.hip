@@ -222,17 +222,39 @@ __device__ __forceinline__ void write_tile(const f32x16 (&acc)[TM][TN], const Ep
   }
 }
 
+// Workgroup -> tile map (tiles_m > 0; a negative tiles_m selects the natural order).
+// Workgroups are dealt to the 8 XCDs round-robin (id % 8), and each
+// XCD has its own L2.  First give every XCD a CONTIGUOUS range of tile numbers, then walk
+// that range in bands of 8 tile-rows, column by column: the ~32 tiles an XCD has in flight
+// form an 8 x 4 patch, so it pulls 12 operand tiles per k-step through its L2 instead of 33.
+__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& bm, int& bn) {
+  const int total = tiles_m * tiles_n;
+  int id = blockIdx.x;
+  if (tiles_m < 0) {   // natural order: consecutive workgroups walk down one column of tiles
+    tiles_m = -tiles_m; bm = id % tiles_m; bn = id / tiles_m; return;
+  }
+  const int per = total / 8;
+  if (id < per * 8) id = (id % 8) * per + id / 8;       // the remainder keeps its natural order
+  constexpr int GM = 8;
+  const int band = id / (GM * tiles_n);
+  const int first = band * GM;
+  const int rows = tiles_m - first < GM ? tiles_m - first : GM;
+  const int in = id - band * GM * tiles_n;
+  bm = first + in % rows;
+  bn = in / rows;
+}
+
 template <int BM, int BN, int BK, int WPE, bool AKM, bool BKM, int EPI>
 __global__ __launch_bounds__(kThreads, WPE) void gemm_kernel(const uint16_t* __restrict__ A, int64_t lda,
                                                              const uint16_t* __restrict__ B, int64_t ldb,
-                                                             int M, int N, int K, int tiles_m, Epi e) {
+                                                             int M, int N, int K, int tiles_m, int tiles_n, Epi e) {
   constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32, KSTEPS = BK / 16;
   constexpr int A_BYTES = tile_bytes(AKM, BM, BK), B_BYTES = tile_bytes(BKM, BN, BK);
   extern __shared__ __align__(16) char smem[];
   constexpr int BUF = A_BYTES + B_BYTES;   // buffer b: A tile at b*BUF, B tile behind it
 
-  // consecutive workgroups walk down a column of tiles: they share the B (weight) tile
-  const int bm = blockIdx.x % tiles_m, bn = blockIdx.x / tiles_m;
+  int bm, bn;
+  tile_of_block(tiles_m, tiles_n, bm, bn);
   const int m0 = bm * BM, n0 = bn * BN;
   const int wave = threadIdx.x >> 6, l = threadIdx.x & 63;
   const int wm0 = (wave & 1) * WM, wn0 = (wave >> 1) * WN;
@@ -400,7 +422,7 @@ __device__ __forceinline__ bf16x8 dtl_frag(const char* lds, int row0, int kk) {
 template <int BM, int BN, int BK, int NS, int WPE, bool AKM, bool BKM, int EPI>
 __global__ __launch_bounds__(kThreads, WPE) void gemm_dtl_kernel(const uint16_t* __restrict__ A, int64_t lda,
                                                                  const uint16_t* __restrict__ B, int64_t ldb,
-                                                                 int M, int N, int K, int tiles_m, Epi e) {
+                                                                 int M, int N, int K, int tiles_m, int tiles_n, Epi e) {
   constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32, KSTEPS = BK / 16;
   constexpr int A_BYTES = dtl_tile_bytes(BM, BK), B_BYTES = dtl_tile_bytes(BN, BK);
   constexpr int BUF = A_BYTES + B_BYTES;
@@ -408,7 +430,8 @@ __global__ __launch_bounds__(kThreads, WPE) void gemm_dtl_kernel(const uint16_t*
   static_assert(LPT * (NS - 2) < 64, "vmcnt range");
   extern __shared__ __align__(1024) char smem[];
 
-  const int bm = blockIdx.x % tiles_m, bn = blockIdx.x / tiles_m;
+  int bm, bn;
+  tile_of_block(tiles_m, tiles_n, bm, bn);
   const int m0 = bm * BM, n0 = bn * BN;
   const int wave = threadIdx.x >> 6;
   const int wm0 = (wave & 1) * WM, wn0 = (wave >> 1) * WN;
@@ -492,10 +515,12 @@ rv_status launch_dtl(const rv_gemm_args& g, hipStream_t st) {
       return RV_E_DEVICE;
     configured = true;
   }
-  const int tm = (g.M + BM - 1) / BM, tn = (g.N + BN - 1) / BN;
+  int tm = (g.M + BM - 1) / BM, tn = (g.N + BN - 1) / BN;
   Epi e{g.out, g.ldo, g.out2, g.bias, g.resid, g.ldr, g.zin, nullptr};
-  hipLaunchKernelGGL(kern, dim3(tm * tn), dim3(kThreads), smem, st, g.A, g.lda, g.B, g.ldb, g.M, g.N, g.K,
-                     tm, e);
+  const int ntiles = tm * tn;
+  if (!(BM == 128 && BN == 128)) tm = -tm;   // measured: the XCD-banded map pays only for the small tile
+  hipLaunchKernelGGL(kern, dim3(ntiles), dim3(kThreads), smem, st, g.A, g.lda, g.B, g.ldb, g.M, g.N, g.K,
+                     tm, tn, e);
   return rv_launch_status();
 }
 
@@ -509,10 +534,12 @@ rv_status launch(const rv_gemm_args& g, hipStream_t st) {
       return RV_E_DEVICE;
     configured = true;
   }
-  const int tm = (g.M + BM - 1) / BM, tn = (g.N + BN - 1) / BN;
+  int tm = (g.M + BM - 1) / BM, tn = (g.N + BN - 1) / BN;
   Epi e{g.out, g.ldo, g.out2, g.bias, g.resid, g.ldr, g.zin, nullptr};
-  hipLaunchKernelGGL(kern, dim3(tm * tn), dim3(kThreads), smem, st, g.A, g.lda, g.B, g.ldb, g.M, g.N, g.K,
-                     tm, e);
+  const int ntiles = tm * tn;
+  if (!(BM == 128 && BN == 128)) tm = -tm;   // measured: the XCD-banded map pays only for the small tile
+  hipLaunchKernelGGL(kern, dim3(ntiles), dim3(kThreads), smem, st, g.A, g.lda, g.B, g.ldb, g.M, g.N, g.K,
+                     tm, tn, e);
   return rv_launch_status();
 }
 
@@ -524,7 +551,7 @@ template <bool AKM, bool BKM, int EPI>
 rv_status pick_tile(const rv_gemm_args& g, hipStream_t st) {
   auto tiles = [&](int bm, int bn) { return (long)((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn); };
   int tile = g.tile;
-  if (tile == 0) tile = tiles(256, 256) >= 512 ? 2256 : (tiles(128, 256) >= 512 ? 2192 : 2128);
+  if (tile == 0) tile = tiles(256, 256) >= 1024 ? 2256 : (tiles(128, 256) >= 512 ? 2192 : 2128);
   if (tile == 256) return launch<256, 256, 64, 1, AKM, BKM, EPI>(g, st);
   if (tile == 192) return launch<128, 256, 32, 2, AKM, BKM, EPI>(g, st);
   if (tile == 128) return launch<128, 128, 64, 2, AKM, BKM, EPI>(g, st);
