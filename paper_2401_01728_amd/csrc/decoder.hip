@@ -23,7 +23,7 @@ struct DecPlan {
   // byte offsets inside one block's stash
   size_t s_x, s_m1, s_r1, s_u, s_qkv, s_a, s_lse, s_x1, s_m2, s_r2, s_v2, s_z, s_g, blk_bytes;
   // byte offsets inside the work buffer
-  size_t w_dres, w_dres16, w_dtmp, w_dz, w_dqkv, w_D, w_part, w_ytmp;
+  size_t w_dres, w_dres16, w_dx1_16, w_dtmp, w_dz, w_dqkv, w_D, w_part, w_ytmp;
 };
 
 }  // namespace
@@ -68,6 +68,7 @@ rv_status rv_dec_plan(rv_stage* s) {
   size_t w = 0;
   p->w_dres = w; w += align_up(T * d * 4);
   p->w_dres16 = w; w += align_up(T * d * 2);
+  p->w_dx1_16 = w; w += align_up(T * d * 2);
   p->w_dtmp = w; w += align_up(T * d * 2);
   p->w_dz = w; w += align_up(T * f * 2);
   p->w_dqkv = w; w += align_up(T * 3 * d * 2);
@@ -145,7 +146,8 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
   hipStream_t st = s->st;
   const int T = p.T, d = p.d, f = p.f;
   float* dres = (float*)(s->work + p.w_dres);
-  uint16_t* dres16_buf = (uint16_t*)(s->work + p.w_dres16);
+  uint16_t* dres16_buf = (uint16_t*)(s->work + p.w_dres16);   // bf16 dy of the block below
+  uint16_t* dx1_16 = (uint16_t*)(s->work + p.w_dx1_16);       // bf16 dx1 of the current block
   uint16_t* dtmp = (uint16_t*)(s->work + p.w_dtmp);
   uint16_t* dz = (uint16_t*)(s->work + p.w_dz);
   uint16_t* dqkv = (uint16_t*)(s->work + p.w_dqkv);
@@ -173,26 +175,36 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
     const uint16_t* v2 = (const uint16_t*)(sb + p.s_v2);
     const uint16_t* z = (const uint16_t*)(sb + p.s_z);
     const uint16_t* g = (const uint16_t*)(sb + p.s_g);
+    // The four weight-gradient products of the block read only stashed activations and the
+    // bf16 gradients produced below; they are collected and issued as ONE grouped launch at
+    // the end of the block.  dy of this block must survive until then: the residual gradient
+    // in bf16 alternates between two buffers.
+    rv_gemm_args wg[4];
+    auto wgrad = [&](int k, const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb, int M, int N, float* out) {
+      wg[k].A = A; wg[k].lda = lda; wg[k].a_kmajor = 1; wg[k].B = B; wg[k].ldb = ldb; wg[k].b_kmajor = 1;
+      wg[k].M = M; wg[k].N = N; wg[k].K = T; wg[k].epi = RV_EPI_F32; wg[k].out = out; wg[k].ldo = N;
+    };
     // feed-forward half
-    RV_TRY(gemm(st, g, f, 1, dres16, d, 1, f, d, T, RV_EPI_F32, gl + p.w2, d));                      // dW2 = g^T dy
+    wgrad(0, g, f, dres16, d, f, d, gl + p.w2);                                                      // dW2 = g^T dy
     RV_TRY(gemm(st, dres16, d, 0, w + p.w2, d, 0, T, f, d, RV_EPI_BF16_DGELU, dz, f, nullptr, nullptr, nullptr, z));
-    RV_TRY(gemm(st, v2, d, 1, dz, f, 1, d, f, T, RV_EPI_F32, gl + p.w1, f));                         // dW1 = v2^T dz
+    wgrad(1, v2, d, dz, f, d, f, gl + p.w1);                                                         // dW1 = v2^T dz
     RV_TRY(rv_colsum_bf16(dz, f, T, f, part, st));
     RV_TRY(rv_reduce_rows(part, cs_parts, f, f, gl + p.b1, st));
     RV_TRY(gemm(st, dz, f, 0, w + p.w1, f, 0, T, d, f, RV_EPI_BF16, dtmp, d));                       // dv2 = dz W1^T
     RV_TRY(rv_ln_bwd(dtmp, x1, (const float*)(sb + p.s_m2), (const float*)(sb + p.s_r2), w + p.ln2g, dres, dres,
-                     dres16_buf, part, T, d, st));
-    dres16 = dres16_buf;
+                     dx1_16, part, T, d, st));
+    dres16 = dx1_16;                 // (the dy buffer stays intact for dW2 in the grouped launch)
     {
       const float* src[3] = {part, part + d, part + 2 * d};
       float* dst[3] = {gl + p.ln2g, gl + p.ln2b, gl + p.bo};                                         // dbo = sum dx1
       RV_TRY(rv_reduce_rows_multi(src, dst, 3, ln_parts, 3 * (int64_t)d, d, st));
     }
     // attention half
-    RV_TRY(gemm(st, a, d, 1, dres16, d, 1, d, d, T, RV_EPI_F32, gl + p.wo, d));                      // dWo = a^T dx1
+    wgrad(2, a, d, dres16, d, d, d, gl + p.wo);                                                      // dWo = a^T dx1
     RV_TRY(gemm(st, dres16, d, 0, w + p.wo, d, 0, T, d, d, RV_EPI_BF16, dtmp, d));                   // da = dx1 Wo^T
     RV_TRY(rv_attn_bwd(qkv, a, dtmp, (const float*)(sb + p.s_lse), Dbuf, dqkv, p.mb, p.S, d, p.H, st));
-    RV_TRY(gemm(st, u, d, 1, dqkv, 3 * d, 1, d, 3 * d, T, RV_EPI_F32, gl + p.wqkv, 3 * d));          // dWqkv
+    wgrad(3, u, d, dqkv, 3 * d, d, 3 * d, gl + p.wqkv);                                              // dWqkv = u^T dqkv
+    RV_TRY(rv_gemm_wgrad_grouped(wg, 4, st));
     RV_TRY(rv_colsum_bf16(dqkv, 3 * d, T, 3 * d, part, st));
     RV_TRY(rv_reduce_rows(part, cs_parts, 3 * d, 3 * d, gl + p.bqkv, st));
     RV_TRY(gemm(st, dqkv, 3 * d, 0, w + p.wqkv, 3 * d, 0, T, d, 3 * d, RV_EPI_BF16, dtmp, d));       // du
@@ -205,6 +217,7 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
       float* dst[3] = {gl + p.ln1g, gl + p.ln1b, l > 0 ? s->grad + (size_t)(l - 1) * p.per_block + p.b2 : nullptr};
       RV_TRY(rv_reduce_rows_multi(src, dst, l > 0 ? 3 : 2, ln_parts, 3 * (int64_t)d, d, st));
     }
+    dres16 = dres16_buf;             // dy of the block below
   }
   return RV_OK;
 }

@@ -419,19 +419,19 @@ __device__ __forceinline__ bf16x8 dtl_frag(const char* lds, int row0, int kk) {
 // s_waitcnt vmcnt(n) only (expcnt, lgkmcnt left at "no wait"); n < 64
 #define RV_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
 
-template <int BM, int BN, int BK, int NS, int WPE, bool AKM, bool BKM, int EPI>
-__global__ __launch_bounds__(kThreads, WPE) void gemm_dtl_kernel(const uint16_t* __restrict__ A, int64_t lda,
-                                                                 const uint16_t* __restrict__ B, int64_t ldb,
-                                                                 int M, int N, int K, int tiles_m, int tiles_n, Epi e) {
+extern __shared__ __align__(1024) char dtl_smem[];
+
+template <int BM, int BN, int BK, int NS, bool AKM, bool BKM, int EPI>
+__device__ __forceinline__ void gemm_dtl_body(const uint16_t* __restrict__ A, int64_t lda,
+                                              const uint16_t* __restrict__ B, int64_t ldb, int M, int N,
+                                              int K, int bm, int bn, const Epi& e) {
   constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32, KSTEPS = BK / 16;
   constexpr int A_BYTES = dtl_tile_bytes(BM, BK), B_BYTES = dtl_tile_bytes(BN, BK);
   constexpr int BUF = A_BYTES + B_BYTES;
   constexpr int LPT = Dtl<AKM, BM, BK>::N + Dtl<BKM, BN, BK>::N;   // loads per lane per tile
   static_assert(LPT * (NS - 2) < 64, "vmcnt range");
-  extern __shared__ __align__(1024) char smem[];
+  char* smem = dtl_smem;
 
-  int bm, bn;
-  tile_of_block(tiles_m, tiles_n, bm, bn);
   const int m0 = bm * BM, n0 = bn * BN;
   const int wave = threadIdx.x >> 6;
   const int wm0 = (wave & 1) * WM, wn0 = (wave >> 1) * WN;
@@ -503,6 +503,40 @@ __global__ __launch_bounds__(kThreads, WPE) void gemm_dtl_kernel(const uint16_t*
     fill = fill + 1 == NS ? 0 : fill + 1;
   }
   write_tile<TM, TN, EPI>(acc, e, m0 + wm0, n0 + wn0, M, N);
+}
+
+template <int BM, int BN, int BK, int NS, int WPE, bool AKM, bool BKM, int EPI>
+__global__ __launch_bounds__(kThreads, WPE) void gemm_dtl_kernel(const uint16_t* __restrict__ A, int64_t lda,
+                                                                 const uint16_t* __restrict__ B, int64_t ldb,
+                                                                 int M, int N, int K, int tiles_m, int tiles_n, Epi e) {
+  int bm, bn;
+  tile_of_block(tiles_m, tiles_n, bm, bn);
+  gemm_dtl_body<BM, BN, BK, NS, AKM, BKM, EPI>(A, lda, B, ldb, M, N, K, bm, bn, e);
+}
+
+// Several independent products of one kind in a single launch (the four weight-gradient
+// products of a decoder block): a workgroup finds its problem from the running tile count.
+// One launch fills the chip where four small grids would each leave most CUs idle.
+struct GroupedProblem {
+  const uint16_t* A; const uint16_t* B; float* out;
+  int lda, ldb, ldo, M, N, K, tiles_m, first_tile;
+};
+struct GroupedArgs {
+  GroupedProblem p[RV_GEMM_GROUP_MAX];
+  int count;
+};
+
+template <int BM, int BN, int BK, int NS, int WPE>
+__global__ __launch_bounds__(kThreads, WPE) void gemm_dtl_grouped_wgrad_kernel(GroupedArgs ga) {
+  int pi = 0;
+#pragma unroll
+  for (int k = 1; k < RV_GEMM_GROUP_MAX; ++k)
+    if (k < ga.count && (int)blockIdx.x >= ga.p[k].first_tile) pi = k;
+  const GroupedProblem& q = ga.p[pi];
+  const int local = blockIdx.x - q.first_tile;
+  Epi e{q.out, q.ldo, nullptr, nullptr, nullptr, 0, nullptr, nullptr};
+  gemm_dtl_body<BM, BN, BK, NS, true, true, EPI_F32>(q.A, q.lda, q.B, q.ldb, q.M, q.N, q.K, local % q.tiles_m,
+                                                     local / q.tiles_m, e);
 }
 
 template <int BM, int BN, int BK, int NS, int WPE, bool AKM, bool BKM, int EPI>
@@ -595,6 +629,39 @@ rv_status rv_gemm_bf16(const rv_gemm_args& g, hipStream_t st) {
     if (g.epi == EPI_F32) return pick_tile<true, true, EPI_F32>(g, st);
   }
   return RV_E_INVAL;
+}
+
+rv_status rv_gemm_wgrad_grouped(const rv_gemm_args* gs, int count, hipStream_t st) {
+  if (!gs || count < 1 || count > RV_GEMM_GROUP_MAX) return RV_E_INVAL;
+  constexpr int BM = 128, BN = 128, BK = 64, NS = 2;
+  GroupedArgs ga;
+  int tiles = 0;
+  for (int k = 0; k < count; ++k) {
+    const rv_gemm_args& g = gs[k];
+    if (!g.A || !g.B || !g.out || !g.a_kmajor || !g.b_kmajor || g.epi != EPI_F32) return RV_E_INVAL;
+    if (g.M < 8 || g.N < 8 || g.K < 64 || g.K % 64 || g.N % 8 || g.M % 8 || g.lda % 8 || g.ldb % 8 || g.ldo % 4)
+      return RV_E_INVAL;
+    if ((((uintptr_t)g.A) | ((uintptr_t)g.B) | ((uintptr_t)g.out)) & 15) return RV_E_INVAL;
+    if ((int64_t)g.K * g.lda >= (1ll << 31) || (int64_t)g.K * g.ldb >= (1ll << 31)) return RV_E_INVAL;
+    GroupedProblem& q = ga.p[k];
+    q.A = g.A; q.B = g.B; q.out = (float*)g.out;
+    q.lda = (int)g.lda; q.ldb = (int)g.ldb; q.ldo = (int)g.ldo; q.M = g.M; q.N = g.N; q.K = g.K;
+    q.tiles_m = (g.M + BM - 1) / BM;
+    q.first_tile = tiles;
+    tiles += q.tiles_m * ((g.N + BN - 1) / BN);
+  }
+  for (int k = count; k < RV_GEMM_GROUP_MAX; ++k) ga.p[k] = ga.p[0];
+  ga.count = count;
+  constexpr int smem = NS * (dtl_tile_bytes(BM, BK) + dtl_tile_bytes(BN, BK));
+  static bool configured = false;
+  auto kern = gemm_dtl_grouped_wgrad_kernel<BM, BN, BK, NS, 2>;
+  if (!configured) {
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
+      return RV_E_DEVICE;
+    configured = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(tiles), dim3(kThreads), smem, st, ga);
+  return rv_launch_status();
 }
 
 extern "C" rv_status rv_k_gemm_bf16(const void* A, int64_t lda, int a_kmajor, const void* B, int64_t ldb,

@@ -24,6 +24,9 @@ struct rv_gemm_args {
   int tile = 0;                           // 0 = choose, 128 or 256 = force
 };
 rv_status rv_gemm_bf16(const rv_gemm_args& g, hipStream_t st);
+// up to RV_GEMM_GROUP_MAX weight-gradient products (both operands k-major, fp32 output) in one launch
+#define RV_GEMM_GROUP_MAX 4
+rv_status rv_gemm_wgrad_grouped(const rv_gemm_args* gs, int count, hipStream_t st);
 
 // ---- norm.hip ---------------------------------------------------------------------
 rv_status rv_ln_fwd(const void* x, int x_is_bf16, float* xcopy, const uint16_t* gamma, const uint16_t* beta,
