@@ -346,18 +346,18 @@ __global__ __launch_bounds__(kThreads, WPE) void gemm_kernel(const uint16_t* __r
 // opens tile t, so a tile has NS-1 k-steps of compute time to arrive.
 __host__ __device__ constexpr int dtl_tile_bytes(int rows, int bk) { return rows * bk * 2; }
 
-template <bool KM, int ROWS, int BK>
+template <bool KM, int ROWS, int BK, int NW>
 struct Dtl {
-  static constexpr int N = ROWS * BK / 8 / kThreads;   // loads per lane per tile
+  static constexpr int N = ROWS * BK / 8 / (64 * NW);   // loads per lane per tile
   int off[N];
 };
 
-template <bool KM, int ROWS, int BK>
-__device__ __forceinline__ void dtl_init(Dtl<KM, ROWS, BK>& s, int64_t ld, int r0, int rows) {
+template <bool KM, int ROWS, int BK, int NW>
+__device__ __forceinline__ void dtl_init(Dtl<KM, ROWS, BK, NW>& s, int64_t ld, int r0, int rows) {
   const int wave = threadIdx.x >> 6, l = threadIdx.x & 63;
 #pragma unroll
-  for (int i = 0; i < Dtl<KM, ROWS, BK>::N; ++i) {
-    const int slot = (i * 4 + wave) * 64 + l;
+  for (int i = 0; i < Dtl<KM, ROWS, BK, NW>::N; ++i) {
+    const int slot = (i * NW + wave) * 64 + l;
     if (!KM) {
       constexpr int CPR = BK / 8, R256 = 256 / (BK * 2);
       const int row = slot / CPR, c = (slot % CPR) ^ ((row / R256) % CPR);
@@ -374,18 +374,18 @@ __device__ __forceinline__ void dtl_init(Dtl<KM, ROWS, BK>& s, int64_t ld, int r
   }
 }
 
-template <bool KM, int ROWS, int BK>
-__device__ __forceinline__ void dtl_issue(const Dtl<KM, ROWS, BK>& s, const uint16_t* __restrict__ g,
+template <bool KM, int ROWS, int BK, int NW>
+__device__ __forceinline__ void dtl_issue(const Dtl<KM, ROWS, BK, NW>& s, const uint16_t* __restrict__ g,
                                           int64_t ld, int k0, char* lds) {
   const uint16_t* base = KM ? g + (int64_t)k0 * ld : g + k0;
   const int wave = threadIdx.x >> 6;
 #pragma unroll
-  for (int i = 0; i < Dtl<KM, ROWS, BK>::N; ++i) {
+  for (int i = 0; i < Dtl<KM, ROWS, BK, NW>::N; ++i) {
     // LDS byte address of this wave's 1 KiB block (wave-uniform, goes to M0; the hardware
     // adds 16 * lane).  Issued as inline assembly: the compiler would otherwise make every
     // later LDS read wait for ALL outstanding loads, which defeats the ring.  The kernel
     // orders them itself with explicit vmcnt waits and barriers.
-    const int m0v = __builtin_amdgcn_readfirstlane((int)(size_t)lds + (i * 4 + wave) * 1024);
+    const int m0v = __builtin_amdgcn_readfirstlane((int)(size_t)lds + (i * NW + wave) * 1024);
     const uint16_t* src = base + s.off[i];
     asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                  :
@@ -421,14 +421,15 @@ __device__ __forceinline__ bf16x8 dtl_frag(const char* lds, int row0, int kk) {
 
 extern __shared__ __align__(1024) char dtl_smem[];
 
-template <int BM, int BN, int BK, int NS, bool AKM, bool BKM, int EPI>
+template <int BM, int BN, int BK, int NS, int NW, bool AKM, bool BKM, int EPI>
 __device__ __forceinline__ void gemm_dtl_body(const uint16_t* __restrict__ A, int64_t lda,
                                               const uint16_t* __restrict__ B, int64_t ldb, int M, int N,
                                               int K, int bm, int bn, const Epi& e) {
-  constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32, KSTEPS = BK / 16;
+  // NW waves laid out 2 (m) x NW/2 (n)
+  constexpr int WM = BM / 2, WN = BN / (NW / 2), TM = WM / 32, TN = WN / 32, KSTEPS = BK / 16;
   constexpr int A_BYTES = dtl_tile_bytes(BM, BK), B_BYTES = dtl_tile_bytes(BN, BK);
   constexpr int BUF = A_BYTES + B_BYTES;
-  constexpr int LPT = Dtl<AKM, BM, BK>::N + Dtl<BKM, BN, BK>::N;   // loads per lane per tile
+  constexpr int LPT = Dtl<AKM, BM, BK, NW>::N + Dtl<BKM, BN, BK, NW>::N;   // loads per lane per tile
   static_assert(LPT * (NS - 2) < 64, "vmcnt range");
   char* smem = dtl_smem;
 
@@ -444,16 +445,16 @@ __device__ __forceinline__ void gemm_dtl_body(const uint16_t* __restrict__ A, in
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  Dtl<AKM, BM, BK> da;
-  Dtl<BKM, BN, BK> db;
-  dtl_init<AKM, BM, BK>(da, lda, m0, M);
-  dtl_init<BKM, BN, BK>(db, ldb, n0, N);
+  Dtl<AKM, BM, BK, NW> da;
+  Dtl<BKM, BN, BK, NW> db;
+  dtl_init<AKM, BM, BK, NW>(da, lda, m0, M);
+  dtl_init<BKM, BN, BK, NW>(db, ldb, n0, N);
   const int nk = K / BK;
 #pragma unroll
   for (int t = 0; t < NS - 1; ++t)
     if (t < nk) {
-      dtl_issue<AKM, BM, BK>(da, A, lda, t * BK, smem + t * BUF);
-      dtl_issue<BKM, BN, BK>(db, B, ldb, t * BK, smem + t * BUF + A_BYTES);
+      dtl_issue<AKM, BM, BK, NW>(da, A, lda, t * BK, smem + t * BUF);
+      dtl_issue<BKM, BN, BK, NW>(db, B, ldb, t * BK, smem + t * BUF + A_BYTES);
     }
   int stage = 0;               // ring slot of tile `it`
   int fill = NS - 1;           // ring slot the next issued tile goes to
@@ -465,8 +466,8 @@ __device__ __forceinline__ void gemm_dtl_body(const uint16_t* __restrict__ A, in
     else RV_WAIT_VMCNT(0);
     __syncthreads();           // everyone's part of tile `it` is in LDS; everyone left tile it-1
     if (it + NS - 1 < nk) {
-      dtl_issue<AKM, BM, BK>(da, A, lda, (it + NS - 1) * BK, smem + fill * BUF);
-      dtl_issue<BKM, BN, BK>(db, B, ldb, (it + NS - 1) * BK, smem + fill * BUF + A_BYTES);
+      dtl_issue<AKM, BM, BK, NW>(da, A, lda, (it + NS - 1) * BK, smem + fill * BUF);
+      dtl_issue<BKM, BN, BK, NW>(db, B, ldb, (it + NS - 1) * BK, smem + fill * BUF + A_BYTES);
     }
     const char* curA = smem + stage * BUF;
     const char* curB = curA + A_BYTES;
@@ -505,13 +506,13 @@ __device__ __forceinline__ void gemm_dtl_body(const uint16_t* __restrict__ A, in
   write_tile<TM, TN, EPI>(acc, e, m0 + wm0, n0 + wn0, M, N);
 }
 
-template <int BM, int BN, int BK, int NS, int WPE, bool AKM, bool BKM, int EPI>
-__global__ __launch_bounds__(kThreads, WPE) void gemm_dtl_kernel(const uint16_t* __restrict__ A, int64_t lda,
+template <int BM, int BN, int BK, int NS, int NW, int WPE, bool AKM, bool BKM, int EPI>
+__global__ __launch_bounds__(64 * NW, WPE) void gemm_dtl_kernel(const uint16_t* __restrict__ A, int64_t lda,
                                                                  const uint16_t* __restrict__ B, int64_t ldb,
                                                                  int M, int N, int K, int tiles_m, int tiles_n, Epi e) {
   int bm, bn;
   tile_of_block(tiles_m, tiles_n, bm, bn);
-  gemm_dtl_body<BM, BN, BK, NS, AKM, BKM, EPI>(A, lda, B, ldb, M, N, K, bm, bn, e);
+  gemm_dtl_body<BM, BN, BK, NS, NW, AKM, BKM, EPI>(A, lda, B, ldb, M, N, K, bm, bn, e);
 }
 
 // Several independent products of one kind in a single launch (the four weight-gradient
@@ -535,15 +536,15 @@ __global__ __launch_bounds__(kThreads, WPE) void gemm_dtl_grouped_wgrad_kernel(G
   const GroupedProblem& q = ga.p[pi];
   const int local = blockIdx.x - q.first_tile;
   Epi e{q.out, q.ldo, nullptr, nullptr, nullptr, 0, nullptr, nullptr};
-  gemm_dtl_body<BM, BN, BK, NS, true, true, EPI_F32>(q.A, q.lda, q.B, q.ldb, q.M, q.N, q.K, local % q.tiles_m,
+  gemm_dtl_body<BM, BN, BK, NS, 4, true, true, EPI_F32>(q.A, q.lda, q.B, q.ldb, q.M, q.N, q.K, local % q.tiles_m,
                                                      local / q.tiles_m, e);
 }
 
-template <int BM, int BN, int BK, int NS, int WPE, bool AKM, bool BKM, int EPI>
+template <int BM, int BN, int BK, int NS, int NW, int WPE, bool AKM, bool BKM, int EPI>
 rv_status launch_dtl(const rv_gemm_args& g, hipStream_t st) {
   constexpr int smem = NS * (dtl_tile_bytes(BM, BK) + dtl_tile_bytes(BN, BK));
   static bool configured = false;
-  auto kern = gemm_dtl_kernel<BM, BN, BK, NS, WPE, AKM, BKM, EPI>;
+  auto kern = gemm_dtl_kernel<BM, BN, BK, NS, NW, WPE, AKM, BKM, EPI>;
   if (!configured) {
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
       return RV_E_DEVICE;
@@ -553,7 +554,7 @@ rv_status launch_dtl(const rv_gemm_args& g, hipStream_t st) {
   Epi e{g.out, g.ldo, g.out2, g.bias, g.resid, g.ldr, g.zin, nullptr};
   const int ntiles = tm * tn;
   if (!(BM == 128 && BN == 128)) tm = -tm;   // measured: the XCD-banded map pays only for the small tile
-  hipLaunchKernelGGL(kern, dim3(ntiles), dim3(kThreads), smem, st, g.A, g.lda, g.B, g.ldb, g.M, g.N, g.K,
+  hipLaunchKernelGGL(kern, dim3(ntiles), dim3(64 * NW), smem, st, g.A, g.lda, g.B, g.ldb, g.M, g.N, g.K,
                      tm, tn, e);
   return rv_launch_status();
 }
@@ -578,20 +579,32 @@ rv_status launch(const rv_gemm_args& g, hipStream_t st) {
 }
 
 // Tile choice (codes >= 2000: direct-to-LDS ring; others: register-staged double buffer).
-// 256x256 (one workgroup per CU, 128x128 per wave) has the lowest LDS traffic per MFMA;
-// 128x256 (two workgroups per CU, 64x128 per wave) overlaps one workgroup's barrier and
-// epilogue phases with the other's MFMAs; 128x128 fills the chip on small outputs.
+//   5256  256x256, eight waves of 128x64, BK 64, two stages, one workgroup per CU: lowest
+//         LDS traffic per MFMA, two waves per SIMD cover each other's barrier stalls;
+//   2192  128x256, four waves of 64x128, BK 32, three stages, two workgroups per CU;
+//   2128  128x128, four waves of 64x64, BK 64, two stages, two workgroups per CU: fills the
+//         chip on small outputs.
+// The automatic choice minimises  rounds * tile_area * workgroups_per_CU / efficiency  with
+// rounds = ceil(tiles / (256 CUs * workgroups_per_CU)); efficiencies are measured ratios.
 template <bool AKM, bool BKM, int EPI>
 rv_status pick_tile(const rv_gemm_args& g, hipStream_t st) {
-  auto tiles = [&](int bm, int bn) { return (long)((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn); };
+  auto cost = [&](int bm, int bn, int bpc, double eff) {
+    const long tiles = (long)((g.M + bm - 1) / bm) * ((g.N + bn - 1) / bn);
+    const long rounds = (tiles + 256 * bpc - 1) / (256 * bpc);
+    return (double)rounds * bm * bn * bpc / eff;
+  };
   int tile = g.tile;
-  if (tile == 0) tile = tiles(256, 256) >= 1024 ? 2256 : (tiles(128, 256) >= 512 ? 2192 : 2128);
+  if (tile == 0) {
+    const double c256 = cost(256, 256, 1, 1.0), c192 = cost(128, 256, 2, 0.92), c128 = cost(128, 128, 2, 0.85);
+    tile = c256 <= c192 && c256 <= c128 ? 5256 : (c192 <= c128 ? 2192 : 2128);
+  }
   if (tile == 256) return launch<256, 256, 64, 1, AKM, BKM, EPI>(g, st);
   if (tile == 192) return launch<128, 256, 32, 2, AKM, BKM, EPI>(g, st);
   if (tile == 128) return launch<128, 128, 64, 2, AKM, BKM, EPI>(g, st);
-  if (tile == 2256) return launch_dtl<256, 256, 32, 4, 1, AKM, BKM, EPI>(g, st);
-  if (tile == 2192) return launch_dtl<128, 256, 32, 3, 2, AKM, BKM, EPI>(g, st);
-  if (tile == 2128) return launch_dtl<128, 128, 64, 2, 2, AKM, BKM, EPI>(g, st);
+  if (tile == 2256) return launch_dtl<256, 256, 32, 4, 4, 1, AKM, BKM, EPI>(g, st);
+  if (tile == 2192) return launch_dtl<128, 256, 32, 3, 4, 2, AKM, BKM, EPI>(g, st);
+  if (tile == 2128) return launch_dtl<128, 128, 64, 2, 4, 2, AKM, BKM, EPI>(g, st);
+  if (tile == 5256) return launch_dtl<256, 256, 64, 2, 8, 2, AKM, BKM, EPI>(g, st);
   return RV_E_INVAL;
 }
 

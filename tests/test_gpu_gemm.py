@@ -22,7 +22,7 @@ SHAPES = [(256, 256, 64), (128, 128, 128), (512, 384, 192), (200, 320, 256), (10
 
 
 @pytest.mark.parametrize("M,N,K", SHAPES)
-@pytest.mark.parametrize("tile", [128, 192, 256, 2128, 2192, 2256])
+@pytest.mark.parametrize("tile", [128, 192, 256, 2128, 2192, 2256, 5256])
 def test_forward_product_and_epilogues(M, N, K, tile):
     from paper_2401_01728_amd import kernels as k
     x, x64 = bf16_normal(1, 0, (M, K))
@@ -48,7 +48,7 @@ def test_forward_product_and_epilogues(M, N, K, tile):
 
 
 @pytest.mark.parametrize("M,N,K", SHAPES)
-@pytest.mark.parametrize("tile", [128, 192, 256, 2128, 2192, 2256])
+@pytest.mark.parametrize("tile", [128, 192, 256, 2128, 2192, 2256, 5256])
 def test_input_gradient_product(M, N, K, tile):
     """dx[M, N] = dy[M, K] W^T with W stored [N, K] (its rows are the output columns)."""
     from paper_2401_01728_amd import kernels as k
@@ -65,7 +65,7 @@ def test_input_gradient_product(M, N, K, tile):
 
 
 @pytest.mark.parametrize("M,N,K", SHAPES)
-@pytest.mark.parametrize("tile", [128, 192, 256, 2128, 2192, 2256])
+@pytest.mark.parametrize("tile", [128, 192, 256, 2128, 2192, 2256, 5256])
 def test_weight_gradient_product(M, N, K, tile):
     """dW[M, N] = x^T dy with x [K, M] and dy [K, N]: contraction over the slow dimension."""
     from paper_2401_01728_amd import kernels as k
