@@ -8,7 +8,7 @@
 // is bound by HBM: (C+1)*4 bytes per element (+4 with a folded-in gradient; 2C*4 with
 // write-back).
 //
-// Layout: one workgroup owns TILE consecutive elements.  Chunks are millions of
+// Layout: one workgroup owns a tile of TILE consecutive elements.  Chunks are millions of
 // elements long, so almost every tile lies inside one chunk: its rotation j is
 // wave-uniform, the C replica base pointers are fetched with scalar loads in rotated
 // order and each lane streams C independent 16-byte loads before the first add.
@@ -28,8 +28,8 @@ struct RepTable {
 };
 
 constexpr int kThreads = 256;
-constexpr int kVecPerThread = 2;                       // float4 per lane
-constexpr int kTile = kThreads * kVecPerThread * 4;    // elements per workgroup
+constexpr int kVecPerThread = 1;                       // float4 per lane
+constexpr int kTile = kThreads * kVecPerThread * 4;    // elements per tile
 
 // Owning chunk of element i: ring r = ceil((i+1) R / n) - 1, then the same rule inside
 // the ring's segment.
@@ -53,44 +53,42 @@ __device__ __forceinline__ float elem_mean(const RepTable& tab, int C, int j, ui
   return __fdiv_rn(acc, (float)C);
 }
 
+// The C replica base pointers are fetched with scalar loads in ring order starting at j
+// (wave-uniform), every lane issues its C independent 16-byte loads, then adds them in
+// that order.  (A compile-time rotation of the SUM order over naturally ordered loads was
+// tried: the compiler folds the C unrolled variants back into a dynamically indexed
+// register array in scratch memory, which costs a third of the bandwidth.)
 template <int C, bool HAS_GRAD>
 __device__ __forceinline__ void tile_fast(const RepTable& tab, int j, uint64_t base, float* out,
                                           int write_back, const float* grad, int gr, float eta) {
-  const float invC_num = (float)C;
-  f4 v[kVecPerThread][C];
+  const float c_num = (float)C;
+  j = __builtin_amdgcn_readfirstlane(j);
 #pragma unroll
   for (int u = 0; u < kVecPerThread; ++u) {
-    uint64_t e = base + (uint64_t)(u * kThreads + threadIdx.x) * 4;
+    const uint64_t e = base + (uint64_t)(u * kThreads + threadIdx.x) * 4;
+    f4 v[C];
 #pragma unroll
     for (int s = 0; s < C; ++s) {
       int c = j + s; if (c >= C) c -= C;
-      c = __builtin_amdgcn_readfirstlane(c);
-      const f4* p = reinterpret_cast<const f4*>(tab.p[c] + e);
-      v[u][s] = __builtin_nontemporal_load(p);
+      v[s] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(tab.p[c] + e));
       if (HAS_GRAD && c == gr) {
-        f4 g = __builtin_nontemporal_load(reinterpret_cast<const f4*>(grad + e));
-        v[u][s].x = __fsub_rn(v[u][s].x, __fmul_rn(g.x, eta));
-        v[u][s].y = __fsub_rn(v[u][s].y, __fmul_rn(g.y, eta));
-        v[u][s].z = __fsub_rn(v[u][s].z, __fmul_rn(g.z, eta));
-        v[u][s].w = __fsub_rn(v[u][s].w, __fmul_rn(g.w, eta));
+        const f4 g = __builtin_nontemporal_load(reinterpret_cast<const f4*>(grad + e));
+        v[s].x = __fsub_rn(v[s].x, __fmul_rn(g.x, eta));
+        v[s].y = __fsub_rn(v[s].y, __fmul_rn(g.y, eta));
+        v[s].z = __fsub_rn(v[s].z, __fmul_rn(g.z, eta));
+        v[s].w = __fsub_rn(v[s].w, __fmul_rn(g.w, eta));
       }
     }
-  }
-#pragma unroll
-  for (int u = 0; u < kVecPerThread; ++u) {
-    uint64_t e = base + (uint64_t)(u * kThreads + threadIdx.x) * 4;
-    f4 a = v[u][0];
+    f4 a = v[0];
 #pragma unroll
     for (int s = 1; s < C; ++s) {
-      a.x = __fadd_rn(a.x, v[u][s].x);
-      a.y = __fadd_rn(a.y, v[u][s].y);
-      a.z = __fadd_rn(a.z, v[u][s].z);
-      a.w = __fadd_rn(a.w, v[u][s].w);
+      a.x = __fadd_rn(a.x, v[s].x); a.y = __fadd_rn(a.y, v[s].y);
+      a.z = __fadd_rn(a.z, v[s].z); a.w = __fadd_rn(a.w, v[s].w);
     }
-    a.x = __fdiv_rn(a.x, invC_num);
-    a.y = __fdiv_rn(a.y, invC_num);
-    a.z = __fdiv_rn(a.z, invC_num);
-    a.w = __fdiv_rn(a.w, invC_num);
+    a.x = __fdiv_rn(a.x, c_num);
+    a.y = __fdiv_rn(a.y, c_num);
+    a.z = __fdiv_rn(a.z, c_num);
+    a.w = __fdiv_rn(a.w, c_num);
     if (out != nullptr) __builtin_nontemporal_store(a, reinterpret_cast<f4*>(out + e));
     if (write_back) {
 #pragma unroll
@@ -100,38 +98,55 @@ __device__ __forceinline__ void tile_fast(const RepTable& tab, int j, uint64_t b
   }
 }
 
-// C == 0 instantiates the generic (runtime-C) kernel, which only has the element path.
+// floor(x / d) for x < 2^52 from an fp64 estimate (inv_d = 1/d rounded) and one exact
+// correction step: the estimate is within one of the quotient, q*d fits in 64 bits.
+__device__ __forceinline__ uint64_t floor_div(uint64_t x, uint64_t d, double inv_d) {
+  uint64_t q = (uint64_t)((double)x * inv_d);
+  if (q * d > x) --q;
+  else if ((q + 1) * d <= x) ++q;
+  return q;
+}
+
+struct DivConsts {
+  double inv_n, inv_R, inv_C;
+};
+
+// Chunk that owns element i and the (exclusive) end of that chunk: the same arithmetic as
+// chunk_of, without 64-bit integer division (it runs once per workgroup).
+__device__ __forceinline__ void locate(uint64_t i, uint64_t n, int R, int C, const DivConsts& dc, int& j,
+                                       uint64_t& chunk_end) {
+  const uint64_t r = floor_div((i + 1) * (uint64_t)R - 1, n, dc.inv_n);
+  const uint64_t lo = floor_div(r * n, (uint64_t)R, dc.inv_R), hi = floor_div((r + 1) * n, (uint64_t)R, dc.inv_R);
+  const uint64_t s = hi - lo;
+  j = (int)floor_div((i - lo + 1) * (uint64_t)C - 1, s, 1.0 / (double)s);
+  chunk_end = lo + floor_div((uint64_t)(j + 1) * s, (uint64_t)C, dc.inv_C);
+}
+
+// One workgroup per tile.  C == 0 instantiates the generic (runtime-C) kernel, which only
+// has the element path.
 template <int CT, bool HAS_GRAD>
 __global__ __launch_bounds__(kThreads) void average_kernel(RepTable tab, int Crt, uint64_t n, int R,
                                                            float* out, int write_back,
                                                            const float* grad, int gr, float eta,
-                                                           int aligned) {
+                                                           int aligned, DivConsts dc) {
   const int C = CT > 0 ? CT : Crt;
-  const uint64_t base = (uint64_t)blockIdx.x * kTile;
-  __shared__ int sh_first, sh_last;
-  if (threadIdx.x == 0) {
-    uint64_t last = base + kTile - 1;
-    sh_first = chunk_of(base, n, R, C);
-    sh_last = last < n ? chunk_of(last, n, R, C) : -1;
-    // a tile may also cross a ring boundary while staying in "chunk j" of two rings
-    if (last < n) {
-      uint64_t r0 = ((base + 1) * (uint64_t)R - 1) / n, r1 = ((last + 1) * (uint64_t)R - 1) / n;
-      if (r0 != r1) sh_last = -1;
-    }
-  }
-  __syncthreads();
-  const int jf = sh_first, jl = sh_last;
+  const uint64_t base = (uint64_t)blockIdx.x * kTile, last = base + kTile - 1;
   if constexpr (CT > 0) {
-    if (aligned && jf == jl) {
-      tile_fast<CT, HAS_GRAD>(tab, jf, base, out, write_back, grad, gr, eta);
-      return;
+    if (aligned) {
+      int j;
+      uint64_t chunk_end;
+      locate(base, n, R, C, dc, j, chunk_end);   // wave-uniform, no barrier needed
+      if (last < chunk_end) {                    // chunk_end <= n: the tile is whole and inside one chunk
+        tile_fast<CT, HAS_GRAD>(tab, j, base, out, write_back, grad, gr, eta);
+        return;
+      }
     }
   }
   for (int k = threadIdx.x; k < kTile; k += kThreads) {
-    uint64_t i = base + k;
+    const uint64_t i = base + k;
     if (i >= n) break;
-    int j = chunk_of(i, n, R, C);
-    float m = elem_mean(tab, C, j, i, HAS_GRAD ? grad : nullptr, gr, eta);
+    const int je = chunk_of(i, n, R, C);
+    const float m = elem_mean(tab, C, je, i, HAS_GRAD ? grad : nullptr, gr, eta);
     if (out != nullptr) out[i] = m;
     if (write_back)
       for (int c = 0; c < C; ++c) tab.p[c][i] = m;
@@ -141,13 +156,14 @@ __global__ __launch_bounds__(kThreads) void average_kernel(RepTable tab, int Crt
 template <int CT>
 void launch(const RepTable& tab, int C, uint64_t n, int R, float* out, int wb, const float* grad,
             int gr, float eta, int aligned, hipStream_t st) {
-  unsigned blocks = (unsigned)((n + kTile - 1) / kTile);
+  const unsigned blocks = (unsigned)((n + kTile - 1) / kTile);
+  const DivConsts dc{1.0 / (double)n, 1.0 / (double)R, 1.0 / (double)C};
   if (grad)
     hipLaunchKernelGGL((average_kernel<CT, true>), dim3(blocks), dim3(kThreads), 0, st, tab, C, n, R,
-                       out, wb, grad, gr, eta, aligned);
+                       out, wb, grad, gr, eta, aligned, dc);
   else
     hipLaunchKernelGGL((average_kernel<CT, false>), dim3(blocks), dim3(kThreads), 0, st, tab, C, n, R,
-                       out, wb, grad, gr, eta, aligned);
+                       out, wb, grad, gr, eta, aligned, dc);
 }
 
 }  // namespace
