@@ -102,23 +102,24 @@ def gelu_grad(z):
 def causal_attention_fwd(q, k, v):
     """q,k,v: [mb,h,S,dh].  Returns a [mb,h,S,dh] and the probabilities."""
     S, dh = q.shape[-2], q.shape[-1]
-    s = np.einsum("bhid,bhjd->bhij", q, k) / np.sqrt(float(dh))
+    s = (q @ np.swapaxes(k, -1, -2)) / np.sqrt(float(dh))          # s[i,j] = q_i . k_j / sqrt(dh)
     i = np.arange(S)[:, None]
     j = np.arange(S)[None, :]
     s = np.where(j <= i, s, -np.inf)
     s = s - s.max(axis=-1, keepdims=True)
     e = np.exp(s)
     p = e / e.sum(axis=-1, keepdims=True)
-    return np.einsum("bhij,bhjd->bhid", p, v), p
+    return p @ v, p                                               # a_i = sum_j p_ij v_j
 
 
 def causal_attention_bwd(da, q, k, v, p):
     dh = q.shape[-1]
-    dv = np.einsum("bhij,bhid->bhjd", p, da)
-    dp = np.einsum("bhid,bhjd->bhij", da, v)
+    pt = np.swapaxes(p, -1, -2)
+    dv = pt @ da                                                  # dv_j = sum_i p_ij da_i
+    dp = da @ np.swapaxes(v, -1, -2)                              # dp_ij = da_i . v_j
     ds = p * (dp - (dp * p).sum(axis=-1, keepdims=True))
-    dq = np.einsum("bhij,bhjd->bhid", ds, k) / np.sqrt(float(dh))
-    dk = np.einsum("bhij,bhid->bhjd", ds, q) / np.sqrt(float(dh))
+    dq = (ds @ k) / np.sqrt(float(dh))                            # dq_i = sum_j ds_ij k_j / sqrt(dh)
+    dk = (np.swapaxes(ds, -1, -2) @ q) / np.sqrt(float(dh))       # dk_j = sum_i ds_ij q_i / sqrt(dh)
     return dq, dk, dv
 
 
