@@ -160,21 +160,37 @@ def bench_stage(args, name):
                         "frac": tflops / BF16_PEAK_TFLOPS, "traffic": None, "kernel": "whole stage step",
                         "algorithmic_flops_per_step": flops},
            "wall_ms_per_step": wall_ms}
+    # the dominant kernel on its own: the largest forward product of a block (x W1 with the
+    # GELU epilogue), launched through the per-kernel entry point and timed with HIP events
+    from paper_2401_01728_amd import kernels as kk
+    T, d, f = tokens, c["d"], c["f"]
+    A = torch.empty(T, d, dtype=torch.bfloat16, device="cuda").normal_()
+    B = torch.empty(d, f, dtype=torch.bfloat16, device="cuda").normal_(std=0.02)
+    bias = torch.zeros(f, dtype=torch.bfloat16, device="cuda")
+    z = torch.empty(T, f, dtype=torch.bfloat16, device="cuda"); gl = torch.empty_like(z)
+    kms, _ = events_ms(lambda: kk.gemm_bf16(A, 0, B, 1, T, f, d, kk.EPI_BF16_BIAS_GELU, z, out2=gl, bias=bias), 20, 3)
+    kfl = 2.0 * T * d * f
+    res["roofline_kernel"] = {"kernel": "gemm_dtl_kernel (x W1 + b1, GELU epilogue) M=%d N=%d K=%d" % (T, f, d),
+                              "bound": "mfma", "achieved": kfl / (kms * 1e-3) / 1e12, "peak": BF16_PEAK_TFLOPS,
+                              "unit": "TFLOP/s", "frac": kfl / (kms * 1e-3) / 1e12 / BF16_PEAK_TFLOPS,
+                              "us_per_launch": kms * 1e3, "algorithmic_flops_per_launch": kfl}
     if not args.no_cpu:
         res["cpu_baseline"] = cpu_stage(c)
     return res
 
 
 def cpu_stage(c):
-    """One oracle forward + backward + update of the same stage on one microbatch."""
-    from oracle import stage as ostage, blocks
+    """The oracle's stage step (forward, backward with recomputed forward, update) on a BOUNDED
+    sample: two sequences of the workload's shape instead of the full microbatch."""
+    from oracle import stage as ostage
     from paper_2401_01728_amd.inputs import gen
-    d, f, L = c["d"], c["f"], c["L"]
+    d, f, L, S = c["d"], c["f"], c["L"], c["S"]
+    mb = min(2, c["mb"])
     P = L * (4 * d * d + 2 * d * f + 9 * d + f)
     w = gen.normal_f32(c["seed"], 0, P, 0.0, 0.02).astype(np.float64)
-    n = c["mb"] * c["S"] * d
-    x = gen.bf16_bits_to_f32(gen.normal_bf16_bits(c["seed"], 1000, n)).astype(np.float64).reshape(c["mb"], c["S"], d)
-    dy = gen.bf16_bits_to_f32(gen.normal_bf16_bits(c["seed"], 2000, n, 0.0, 1e-3)).astype(np.float64).reshape(c["mb"], c["S"], d)
+    n = mb * S * d
+    x = gen.bf16_bits_to_f32(gen.normal_bf16_bits(c["seed"], 1000, n)).astype(np.float64).reshape(mb, S, d)
+    dy = gen.bf16_bits_to_f32(gen.normal_bf16_bits(c["seed"], 2000, n, 0.0, 1e-3)).astype(np.float64).reshape(mb, S, d)
     o = ostage.Stage("decoder", 0, c["eta"], w, n_blocks=L, d=d, h=c["h"], f=f)
     t0 = time.perf_counter()
     o.forward(0, x); o.backward(0, dy)
@@ -183,16 +199,16 @@ def cpu_stage(c):
         cores = len(os.sched_getaffinity(0))
     except AttributeError:
         cores = os.cpu_count()
-    return {"value": c["mb"] * c["S"] / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
-            "sample": "one oracle stage step (forward, backward with recomputed forward, update) on one "
-                      "microbatch of the same shape, numpy fp64, %.1f s" % dt}
+    return {"value": mb * S / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": "one oracle stage step (numpy fp64) on %d of the %d sequences of a microbatch, %.1f s"
+                      % (mb, c["mb"], dt)}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default=None)
     ap.add_argument("--rings", type=int, default=4)
     ap.add_argument("--n", type=float, default=None)
