@@ -180,19 +180,21 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(const uint16_t* __re
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub)
           s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_kc<DH>(Ks, sub * 32, kk), qf[kk], s[sub], 0, 0, 0);
+      // running max m is kept in the scaled base-2 domain; the scale (> 0) commutes with max,
+      // so the row max is taken over raw scores and p = exp2(s*c2 - m) is one FMA + one exp
       const bool diag = k0 + TILE - 1 > q0;
       float mx = -INFINITY;
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          float v = s[sub][r] * c2;
+          float v = s[sub][r];
           if (diag && k0 + sub * 32 + acc_row(r, grp) > qi) v = -INFINITY;
           s[sub][r] = v;
           mx = fmaxf(mx, v);
         }
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float mn = fmaxf(m, mx);
+      const float mn = fmaxf(m, mx * c2);
       const float alpha = __builtin_amdgcn_exp2f(m - mn);
       m = mn;
       float ps = 0.f;
@@ -200,7 +202,7 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(const uint16_t* __re
       for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          float p = __builtin_amdgcn_exp2f(s[sub][r] - mn);
+          float p = __builtin_amdgcn_exp2f(__fmaf_rn(s[sub][r], c2, -mn));
           s[sub][r] = p;
           ps += p;
         }

@@ -30,6 +30,10 @@ __device__ __forceinline__ uint16_t rv_f32_to_bf16(float x) {
 __device__ __forceinline__ float rv_bf16_to_f32(uint16_t h) {
   return __uint_as_float(((uint32_t)h) << 16);
 }
+// two fp32 -> packed bf16x2, round to nearest even: one v_cvt_pk_bf16_f32 on gfx950
 __device__ __forceinline__ uint32_t rv_pack_bf16x2(float lo, float hi) {
-  return (uint32_t)rv_f32_to_bf16(lo) | ((uint32_t)rv_f32_to_bf16(hi) << 16);
+  typedef __bf16 rv_bf16x2 __attribute__((ext_vector_type(2)));
+  typedef float rv_f32x2 __attribute__((ext_vector_type(2)));
+  const rv_f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, rv_bf16x2));
 }
