@@ -334,6 +334,69 @@ __global__ __launch_bounds__(kThreads, WPE) void gemm_kernel(const uint16_t* __r
   write_tile<TM, TN, EPI>(acc, e, m0 + wm0, n0 + wn0, M, N);
 }
 
+// bf16 outputs leave through LDS: every wave parks its accumulator tile (after bias / GELU /
+// GELU') as bf16 in a [BM][BN] image of the workgroup tile, then the workgroup writes the
+// image out row by row, 16 bytes per lane, whole 128-byte lines per row segment - instead
+// of 8-byte pieces of 32 different rows per store instruction.  The GELU epilogue makes two
+// trips (pre-activation, then activation).  The image reuses the operand ring.
+__host__ __device__ constexpr int stage_pitch(int bn) { return bn * 2 + 16; }
+__host__ __device__ constexpr bool staged_epi(int epi) {
+  return epi == EPI_BF16 || epi == EPI_BF16_BIAS || epi == EPI_BF16_BIAS_GELU || epi == EPI_BF16_DGELU;
+}
+
+template <int BM, int BN, int NT, int TM, int TN, int EPI>
+__device__ __forceinline__ void write_tile_staged(const f32x16 (&acc)[TM][TN], const Epi& e, int m0, int n0,
+                                                  int wm0, int wn0, int M, int N, char* smem) {
+  constexpr int PITCH = stage_pitch(BN);
+  constexpr int PASSES = EPI == EPI_BF16_BIAS_GELU ? 2 : 1;
+  const int l = threadIdx.x & 63;
+  __syncthreads();   // every wave has finished reading operands from the ring
+#pragma unroll
+  for (int pass = 0; pass < PASSES; ++pass) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int ml = wm0 + i * 32 + (l & 31);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {
+          const int nl = wn0 + j * 32 + 8 * rg + 4 * (l >> 5);
+          const int gm = m0 + ml, gn = n0 + nl;
+          f32x4 a = {acc[i][j][4 * rg], acc[i][j][4 * rg + 1], acc[i][j][4 * rg + 2], acc[i][j][4 * rg + 3]};
+          if (EPI == EPI_BF16_BIAS || EPI == EPI_BF16_BIAS_GELU) {
+            if (gn < N) {
+              u32x2 b = *reinterpret_cast<const u32x2*>(e.bias + gn);
+              a.x += __uint_as_float(b.x << 16); a.y += __uint_as_float(b.x & 0xFFFF0000u);
+              a.z += __uint_as_float(b.y << 16); a.w += __uint_as_float(b.y & 0xFFFF0000u);
+            }
+            if (pass == 1) { a.x = gelu_f(a.x); a.y = gelu_f(a.y); a.z = gelu_f(a.z); a.w = gelu_f(a.w); }
+          }
+          if (EPI == EPI_BF16_DGELU) {
+            if (gm < M && gn < N) {
+              u32x2 z = *reinterpret_cast<const u32x2*>(e.zin + (int64_t)gm * e.ldo + gn);
+              a.x *= dgelu_f(__uint_as_float(z.x << 16)); a.y *= dgelu_f(__uint_as_float(z.x & 0xFFFF0000u));
+              a.z *= dgelu_f(__uint_as_float(z.y << 16)); a.w *= dgelu_f(__uint_as_float(z.y & 0xFFFF0000u));
+            }
+          }
+          u32x2 o; o.x = rv_pack_bf16x2(a.x, a.y); o.y = rv_pack_bf16x2(a.z, a.w);
+          *reinterpret_cast<u32x2*>(smem + ml * PITCH + nl * 2) = o;
+        }
+      }
+    }
+    __syncthreads();
+    uint16_t* dst = (uint16_t*)(pass == 0 ? e.out : e.out2);
+    constexpr int CPR = BN / 8;
+    for (int idx = threadIdx.x; idx < BM * CPR; idx += NT) {
+      const int row = idx / CPR, c = idx % CPR;
+      const int gm = m0 + row, gn = n0 + c * 8;
+      if (gm < M && gn < N)
+        *reinterpret_cast<u32x4*>(dst + (int64_t)gm * e.ldo + gn) =
+            *reinterpret_cast<const u32x4*>(smem + row * PITCH + c * 16);
+    }
+    if (pass + 1 < PASSES) __syncthreads();
+  }
+}
+
 // ---- direct-to-LDS pipeline ---------------------------------------------------------------
 // Tiles go global -> LDS with global_load_lds_dwordx4: no staging registers, no LDS write
 // instructions.  One such instruction fills 1 KiB of LDS (lane i -> base + 16 i), so the
@@ -503,7 +566,10 @@ __device__ __forceinline__ void gemm_dtl_body(const uint16_t* __restrict__ A, in
     stage = stage + 1 == NS ? 0 : stage + 1;
     fill = fill + 1 == NS ? 0 : fill + 1;
   }
-  write_tile<TM, TN, EPI>(acc, e, m0 + wm0, n0 + wn0, M, N);
+  if constexpr (staged_epi(EPI))
+    write_tile_staged<BM, BN, 64 * NW, TM, TN, EPI>(acc, e, m0, n0, wm0, wn0, M, N, smem);
+  else
+    write_tile<TM, TN, EPI>(acc, e, m0 + wm0, n0 + wn0, M, N);
 }
 
 template <int BM, int BN, int BK, int NS, int NW, int WPE, bool AKM, bool BKM, int EPI>
@@ -542,7 +608,9 @@ __global__ __launch_bounds__(kThreads, WPE) void gemm_dtl_grouped_wgrad_kernel(G
 
 template <int BM, int BN, int BK, int NS, int NW, int WPE, bool AKM, bool BKM, int EPI>
 rv_status launch_dtl(const rv_gemm_args& g, hipStream_t st) {
-  constexpr int smem = NS * (dtl_tile_bytes(BM, BK) + dtl_tile_bytes(BN, BK));
+  constexpr int ring = NS * (dtl_tile_bytes(BM, BK) + dtl_tile_bytes(BN, BK));
+  constexpr int image = staged_epi(EPI) ? BM * stage_pitch(BN) : 0;
+  constexpr int smem = ring > image ? ring : image;
   static bool configured = false;
   auto kern = gemm_dtl_kernel<BM, BN, BK, NS, NW, WPE, AKM, BKM, EPI>;
   if (!configured) {
