@@ -37,7 +37,7 @@ __device__ __forceinline__ u32x2 f32_to_bf16x4(f32x4 a) {
 // y = LN(x) * gamma + beta.  IN_BF16: x arrives as bf16 (stage input) and is also written
 // out as the fp32 residual stream xcopy.
 template <int NV, bool IN_BF16>
-__global__ __launch_bounds__(kThreads) void ln_fwd_kernel(const void* __restrict__ xin,
+__global__ __launch_bounds__(kThreads, NV <= 4 ? 4 : 1) void ln_fwd_kernel(const void* __restrict__ xin,
                                                           float* __restrict__ xcopy,
                                                           const uint16_t* __restrict__ gamma,
                                                           const uint16_t* __restrict__ beta,
@@ -94,74 +94,101 @@ __global__ __launch_bounds__(kThreads) void ln_fwd_kernel(const void* __restrict
 //   0: sum dy * xh (d gamma)   1: sum dy (d beta)   2: sum dx (bias gradient of the Linear
 //   whose output fed this residual stream).
 constexpr int kRowsPerBlock = 16;
+constexpr int kBwdWaves = 8;
 
-template <int NV>
-__global__ __launch_bounds__(kThreads) void ln_bwd_kernel(const uint16_t* __restrict__ dy,
-                                                          const float* __restrict__ x,
-                                                          const float* __restrict__ mean,
-                                                          const float* __restrict__ rstd,
-                                                          const uint16_t* __restrict__ gamma,
-                                                          const float* dres, float* dx,
-                                                          uint16_t* __restrict__ dx_bf16,
-                                                          float* __restrict__ part, int T, int d) {
-  extern __shared__ __align__(16) float red[];  // [kWaves][d]
+// Eight waves per workgroup.  A row is split over CS waves (CS = 1, 2, 4 for d <= 1024,
+// 2048, 4096) so that a lane never owns more than four 16-byte column groups: the three
+// column accumulators and the row operands stay in ~170 registers for every width.  The
+// 8/CS wave groups take rows round-robin; with CS > 1 the row statistics are combined
+// through LDS (fixed order, one barrier per row, two alternating slots).
+template <int CS>
+__global__ __launch_bounds__(64 * kBwdWaves) void ln_bwd_kernel(const uint16_t* __restrict__ dy,
+                                                                const float* __restrict__ x,
+                                                                const float* __restrict__ mean,
+                                                                const float* __restrict__ rstd,
+                                                                const uint16_t* __restrict__ gamma,
+                                                                const float* dres, float* dx,
+                                                                uint16_t* __restrict__ dx_bf16,
+                                                                float* __restrict__ part, int T, int d) {
+  constexpr int NV = 4, RG = kBwdWaves / CS;
+  extern __shared__ __align__(16) float red[];   // [RG][d] column sums, then [2][RG][CS][2] row statistics
+  float* stat = red + RG * d;
   const int wave = threadIdx.x >> 6, l = threadIdx.x & 63;
-  f32x4 ag[NV], ab[NV], ax[NV], gm[NV];
+  const int cs = wave % CS, rg = wave / CS;
+  const int cbase = cs * 1024 + l * 4;
+  f32x4 ag[NV], ab[NV], ax[NV];
 #pragma unroll
-  for (int i = 0; i < NV; ++i) {
-    ag[i] = 0.f; ab[i] = 0.f; ax[i] = 0.f; gm[i] = 0.f;
-    const int c = l * 4 + 256 * i;
-    if (c < d) gm[i] = bf16x4_to_f32(*reinterpret_cast<const u32x2*>(gamma + c));
-  }
-  for (int rr = wave; rr < kRowsPerBlock; rr += kWaves) {
-    const int row = blockIdx.x * kRowsPerBlock + rr;
-    if (row >= T) break;
-    const float mu = mean[row], r = rstd[row];
-    f32x4 xh[NV], dyv[NV];
+  for (int i = 0; i < NV; ++i) { ag[i] = 0.f; ab[i] = 0.f; ax[i] = 0.f; }
+#pragma unroll 1
+  for (int k = 0; k < kRowsPerBlock / RG; ++k) {
+    const int row = blockIdx.x * kRowsPerBlock + k * RG + rg;
+    const bool valid = row < T;
+    // the three row operands are requested together: one memory round trip per row
+    f32x4 xh[NV], dyv[NV], rs[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int c = cbase + 256 * i;
+      xh[i] = 0.f; dyv[i] = 0.f; rs[i] = 0.f;
+      if (valid && c < d) {
+        xh[i] = *reinterpret_cast<const f32x4*>(x + (int64_t)row * d + c);
+        rs[i] = *reinterpret_cast<const f32x4*>(dres + (int64_t)row * d + c);
+        dyv[i] = bf16x4_to_f32(*reinterpret_cast<const u32x2*>(dy + (int64_t)row * d + c));
+      }
+    }
+    const float mu = valid ? mean[row] : 0.f, r = valid ? rstd[row] : 0.f;
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-      const int c = l * 4 + 256 * i;
+      const int c = cbase + 256 * i;
       if (c < d) {
-        xh[i] = (*reinterpret_cast<const f32x4*>(x + (int64_t)row * d + c) - mu) * r;
-        dyv[i] = bf16x4_to_f32(*reinterpret_cast<const u32x2*>(dy + (int64_t)row * d + c));
-        f32x4 dxh = dyv[i] * gm[i];
-        f32x4 t = dxh * xh[i];
+        xh[i] = (xh[i] - mu) * r;
+        const f32x4 dxh = dyv[i] * bf16x4_to_f32(*reinterpret_cast<const u32x2*>(gamma + c));
+        const f32x4 t = dxh * xh[i];
         s1 += (dxh.x + dxh.y) + (dxh.z + dxh.w);
         s2 += (t.x + t.y) + (t.z + t.w);
       }
     }
-    const float c1 = wave_sum(s1) / (float)d, c2 = wave_sum(s2) / (float)d;
+    s1 = wave_sum(s1); s2 = wave_sum(s2);
+    if (CS > 1) {
+      float* slot = stat + (k & 1) * RG * CS * 2 + rg * CS * 2;
+      if (l == 0) { slot[cs * 2] = s1; slot[cs * 2 + 1] = s2; }
+      __syncthreads();
+      s1 = slot[0]; s2 = slot[1];
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-      const int c = l * 4 + 256 * i;
-      if (c < d) {
-        f32x4 dxh = dyv[i] * gm[i];
-        f32x4 o = (dxh - c1 - xh[i] * c2) * r;
-        o += *reinterpret_cast<const f32x4*>(dres + (int64_t)row * d + c);
-        *reinterpret_cast<f32x4*>(dx + (int64_t)row * d + c) = o;
-        if (dx_bf16) *reinterpret_cast<u32x2*>(dx_bf16 + (int64_t)row * d + c) = f32_to_bf16x4(o);
-        ag[i] += dyv[i] * xh[i];
-        ab[i] += dyv[i];
-        ax[i] += o;
+      for (int q = 1; q < CS; ++q) { s1 += slot[q * 2]; s2 += slot[q * 2 + 1]; }
+    }
+    const float c1 = s1 / (float)d, c2 = s2 / (float)d;
+    if (valid) {
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        const int c = cbase + 256 * i;
+        if (c < d) {
+          const f32x4 dxh = dyv[i] * bf16x4_to_f32(*reinterpret_cast<const u32x2*>(gamma + c));
+          const f32x4 o = (dxh - c1 - xh[i] * c2) * r + rs[i];
+          *reinterpret_cast<f32x4*>(dx + (int64_t)row * d + c) = o;
+          if (dx_bf16) *reinterpret_cast<u32x2*>(dx_bf16 + (int64_t)row * d + c) = f32_to_bf16x4(o);
+          ag[i] += dyv[i] * xh[i];
+          ab[i] += dyv[i];
+          ax[i] += o;
+        }
       }
     }
   }
-  // cross-wave sums, one quantity at a time
+  // column sums across the RG row groups, one quantity at a time, fixed order
   for (int qn = 0; qn < 3; ++qn) {
+    __syncthreads();
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-      const int c = l * 4 + 256 * i;
-      if (c < d) *reinterpret_cast<f32x4*>(red + wave * d + c) = qn == 0 ? ag[i] : (qn == 1 ? ab[i] : ax[i]);
+      const int c = cbase + 256 * i;
+      if (c < d) *reinterpret_cast<f32x4*>(red + rg * d + c) = qn == 0 ? ag[i] : (qn == 1 ? ab[i] : ax[i]);
     }
     __syncthreads();
-    for (int c = threadIdx.x * 4; c < d; c += kThreads * 4) {
+    for (int c = threadIdx.x * 4; c < d; c += 64 * kBwdWaves * 4) {
       f32x4 s = *reinterpret_cast<const f32x4*>(red + c);
 #pragma unroll
-      for (int w = 1; w < kWaves; ++w) s += *reinterpret_cast<const f32x4*>(red + w * d + c);
+      for (int w = 1; w < RG; ++w) s += *reinterpret_cast<const f32x4*>(red + w * d + c);
       *reinterpret_cast<f32x4*>(part + ((int64_t)blockIdx.x * 3 + qn) * d + c) = s;
     }
-    __syncthreads();
   }
 }
 
@@ -264,18 +291,17 @@ int rv_ln_bwd_parts(int T) { return (T + kRowsPerBlock - 1) / kRowsPerBlock; }
 rv_status rv_ln_bwd(const uint16_t* dy, const float* x, const float* mean, const float* rstd,
                     const uint16_t* gamma, const float* dres, float* dx, uint16_t* dx_bf16, float* part,
                     int T, int d, hipStream_t st) {
-  if (!dy || !x || !mean || !rstd || !gamma || !dres || !dx || !part || T < 1 || d < 4 || d % 4)
+  if (!dy || !x || !mean || !rstd || !gamma || !dres || !dx || !part || T < 1 || d < 4 || d % 4 || d > 4096)
     return RV_E_INVAL;
-  const int nv = nv_for(d);
-  if (!nv || d > 4096) return RV_E_INVAL;   // LDS: 4 * d floats
-  dim3 grid(rv_ln_bwd_parts(T)), blk(kThreads);
-  const size_t smem = (size_t)kWaves * d * sizeof(float);
-#define RV_LN_BWD(NV) \
-  hipLaunchKernelGGL((ln_bwd_kernel<NV>), grid, blk, smem, st, dy, x, mean, rstd, gamma, dres, dx, dx_bf16, part, T, d);
-  switch (nv) {
-    case 4: RV_LN_BWD(4) break;
-    case 8: RV_LN_BWD(8) break;
-    default: RV_LN_BWD(16) break;
+  dim3 grid(rv_ln_bwd_parts(T)), blk(64 * kBwdWaves);
+  const int cs = d <= 1024 ? 1 : d <= 2048 ? 2 : 4;
+  const size_t smem = ((size_t)(kBwdWaves / cs) * d + 2 * kBwdWaves * 2) * sizeof(float);
+#define RV_LN_BWD(CS) \
+  hipLaunchKernelGGL((ln_bwd_kernel<CS>), grid, blk, smem, st, dy, x, mean, rstd, gamma, dres, dx, dx_bf16, part, T, d);
+  switch (cs) {
+    case 1: RV_LN_BWD(1) break;
+    case 2: RV_LN_BWD(2) break;
+    default: RV_LN_BWD(4) break;
   }
 #undef RV_LN_BWD
   return rv_launch_status();
