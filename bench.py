@@ -91,6 +91,8 @@ def bench_avg4(args):
     grad = torch.empty(n, dtype=torch.float32, device="cuda"); device.fill_normal_(grad, seed, 99, 0.0, 1e-3)
     out = torch.empty(n, dtype=torch.float32, device="cuda")
     fn = lambda: rv.cluster_average(reps, R, mean_out=out, grad=grad, grad_replica=0, eta=eta)
+    if args.calib_copy:     # a plain copy of known size (n fp32 read + n fp32 written) to scale the HBM counters
+        out.copy_(grad)
     ms, wall_ms = events_ms(fn, args.steps, args.warmup)
     alg_bytes = (C + 2) * 4 * n
     gbs = alg_bytes / (ms * 1e-3) / 1e9
@@ -213,6 +215,7 @@ def main():
     ap.add_argument("--rings", type=int, default=4)
     ap.add_argument("--n", type=float, default=None)
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true", help="avg4: also run one plain 4*n-byte copy (counter calibration)")
     ap.add_argument("--no-overlap", action="store_true",
                     help="issue forward and backward as two calls on one stream (for per-kernel profiles)")
     args = ap.parse_args()
