@@ -170,6 +170,18 @@ rv_status rv_cluster_average(float* const* replicas, int C, size_t n, int R, flo
                              int write_back, const float* grad, int grad_replica, float eta,
                              void* stream);
 
+/*
+ * The same cycle with rings of UNEQUAL size (section 3.2: clusters split the model
+ * differently, a ring covers the parameters two neighbouring peers share, so segment sizes
+ * differ and a peer may sit in several rings).  ring_offsets: host array of R+1 element
+ * offsets, ring_offsets[0] = 0 <= ... <= ring_offsets[R] = n (empty rings allowed),
+ * 1 <= R <= 64.  Ring r owns [ring_offsets[r], ring_offsets[r+1]); chunks, summation order
+ * and every other argument as in rv_cluster_average.  RV_E_INVAL on a malformed table.
+ */
+rv_status rv_cluster_average_v(float* const* replicas, int C, size_t n, const int64_t* ring_offsets,
+                               int R, float* mean_out, int write_back, const float* grad,
+                               int grad_replica, float eta, void* stream);
+
 const char* rv_strerror(rv_status st);
 
 #ifdef __cplusplus

@@ -20,11 +20,13 @@ when the reduce phase of a chunk completes.
 import numpy as np
 
 
-def ring_partition(n, R, C):
-    """bounds[r][j] .. bounds[r][j+1] is chunk j of ring r."""
+def ring_partition(n, R, C, ring_offsets=None):
+    """bounds[r][j] .. bounds[r][j+1] is chunk j of ring r.  ring_offsets (R+1 element
+    offsets) gives rings of unequal size (section 3.2: segment sizes follow the submodel
+    boundaries of the clusters); default: R equal segments."""
     out = []
     for r in range(R):
-        lo, hi = (r * n) // R, ((r + 1) * n) // R
+        lo, hi = ((r * n) // R, ((r + 1) * n) // R) if ring_offsets is None else (ring_offsets[r], ring_offsets[r + 1])
         s = hi - lo
         out.append([lo + (j * s) // C for j in range(C + 1)])
     return out
@@ -41,7 +43,7 @@ def direct_mean(replicas, grad=None, grad_replica=0, eta=0.0):
     return acc / float(len(xs))
 
 
-def multi_ring_allreduce(replicas, R, grad=None, grad_replica=0, eta=0.0, dtype=np.float64):
+def multi_ring_allreduce(replicas, R, grad=None, grad_replica=0, eta=0.0, dtype=np.float64, ring_offsets=None):
     """Round-by-round simulation.  Returns (buffers, rounds, sent) where
     buffers[c] is replica c's vector after the cycle, rounds the number of
     rounds played and sent[r][c] the elements replica c sent on ring r."""
@@ -51,7 +53,7 @@ def multi_ring_allreduce(replicas, R, grad=None, grad_replica=0, eta=0.0, dtype=
     if grad is not None:
         step = (np.asarray(grad, dtype=dtype) * dtype(eta)).astype(dtype)
         buf[grad_replica] = (buf[grad_replica] - step).astype(dtype)
-    bounds = ring_partition(n, R, C)
+    bounds = ring_partition(n, R, C, ring_offsets)
     sent = [[0] * C for _ in range(R)]
     rounds = 0
     # reduce phase: after round s replica c+1 has added chunk (c - s) mod C
@@ -87,7 +89,7 @@ def multi_ring_allreduce(replicas, R, grad=None, grad_replica=0, eta=0.0, dtype=
     return buf, rounds, sent
 
 
-def ring_order_mean_f32(replicas, R, grad=None, grad_replica=0, eta=0.0):
+def ring_order_mean_f32(replicas, R, grad=None, grad_replica=0, eta=0.0, ring_offsets=None):
     """What the rounds above compute, written per chunk, in fp32: chunk j of
     every ring is summed starting at replica j and walking the ring, then
     divided by C.  Same operation order as multi_ring_allreduce(dtype=float32)
@@ -100,7 +102,7 @@ def ring_order_mean_f32(replicas, R, grad=None, grad_replica=0, eta=0.0):
         xs = list(xs)
         xs[grad_replica] = xs[grad_replica] - step
     out = np.empty(n, dtype=np.float32)
-    for bnd in ring_partition(n, R, C):
+    for bnd in ring_partition(n, R, C, ring_offsets):
         for j in range(C):
             lo, hi = bnd[j], bnd[j + 1]
             acc = xs[j % C][lo:hi].copy()

@@ -32,6 +32,8 @@ SYMBOLS = {
     "rv_block_update": (c_int, [c_void_p, c_void_p, c_size_t, c_float, c_void_p, c_void_p]),
     "rv_cluster_average": (c_int, [ctypes.POINTER(c_void_p), c_int, c_size_t, c_int, c_void_p, c_int,
                                    c_void_p, c_int, c_float, c_void_p]),
+    "rv_cluster_average_v": (c_int, [ctypes.POINTER(c_void_p), c_int, c_size_t, ctypes.POINTER(c_int64), c_int,
+                                     c_void_p, c_int, c_void_p, c_int, c_float, c_void_p]),
     "rv_strerror": (ctypes.c_char_p, [c_int]),
 }
 

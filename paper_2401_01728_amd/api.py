@@ -151,8 +151,9 @@ def block_update(w, g, eta, bf16_out=None, stream=None):
 
 
 def cluster_average(replicas, R, mean_out=None, write_back=False, grad=None, grad_replica=0, eta=0.0,
-                    stream=None):
-    """rv_cluster_average over a list of fp32 device vectors."""
+                    stream=None, ring_offsets=None):
+    """rv_cluster_average over a list of fp32 device vectors (rv_cluster_average_v when
+    ring_offsets, R+1 element offsets, is given)."""
     C = len(replicas)
     n = replicas[0].numel() if C else 0
     for r in replicas:
@@ -162,6 +163,12 @@ def cluster_average(replicas, R, mean_out=None, write_back=False, grad=None, gra
     if grad is not None:
         _dev_f32(grad, n)
     arr = (ctypes.c_void_p * max(C, 1))(*[r.data_ptr() for r in replicas])
+    if ring_offsets is not None:
+        offs = (ctypes.c_int64 * len(ring_offsets))(*[int(o) for o in ring_offsets])
+        _check(_lib.lib().rv_cluster_average_v(arr, C, n, offs, len(ring_offsets) - 1, _ptr(mean_out),
+                                               1 if write_back else 0, _ptr(grad), grad_replica, eta,
+                                               _stream_handle(stream)))
+        return mean_out
     _check(_lib.lib().rv_cluster_average(arr, C, n, R, _ptr(mean_out), 1 if write_back else 0, _ptr(grad),
                                          grad_replica, eta, _stream_handle(stream)))
     return mean_out

@@ -41,6 +41,23 @@ __device__ __forceinline__ int chunk_of(uint64_t i, uint64_t n, int R, int C) {
   return (int)(((i - lo + 1) * (uint64_t)C - 1) / s);
 }
 
+// Rings given by explicit boundaries (segments of unequal size, as when clusters split the
+// model differently and a peer sits in several rings): off[0] = 0 <= ... <= off[R] = n.
+#define RV_MAX_EXPLICIT_R 64
+struct RingOffsets {
+  uint64_t off[RV_MAX_EXPLICIT_R + 1];
+};
+__device__ __forceinline__ void ring_of(const RingOffsets& ro, int R, uint64_t i, uint64_t& lo, uint64_t& hi) {
+  int r = 0;
+  while (r + 1 < R && i >= ro.off[r + 1]) ++r;     // empty rings are stepped over
+  lo = ro.off[r]; hi = ro.off[r + 1];
+}
+__device__ __forceinline__ int chunk_of_v(const RingOffsets& ro, int R, uint64_t i, int C) {
+  uint64_t lo, hi;
+  ring_of(ro, R, i, lo, hi);
+  return (int)(((i - lo + 1) * (uint64_t)C - 1) / (hi - lo));
+}
+
 __device__ __forceinline__ float elem_mean(const RepTable& tab, int C, int j, uint64_t i,
                                            const float* grad, int gr, float eta) {
   float acc = 0.f;
@@ -124,18 +141,26 @@ __device__ __forceinline__ void locate(uint64_t i, uint64_t n, int R, int C, con
 
 // One workgroup per tile.  C == 0 instantiates the generic (runtime-C) kernel, which only
 // has the element path.
-template <int CT, bool HAS_GRAD>
+template <int CT, bool HAS_GRAD, bool EXPL>
 __global__ __launch_bounds__(kThreads) void average_kernel(RepTable tab, int Crt, uint64_t n, int R,
                                                            float* out, int write_back,
                                                            const float* grad, int gr, float eta,
-                                                           int aligned, DivConsts dc) {
+                                                           int aligned, DivConsts dc, RingOffsets ro) {
   const int C = CT > 0 ? CT : Crt;
   const uint64_t base = (uint64_t)blockIdx.x * kTile, last = base + kTile - 1;
   if constexpr (CT > 0) {
     if (aligned) {
       int j;
       uint64_t chunk_end;
-      locate(base, n, R, C, dc, j, chunk_end);   // wave-uniform, no barrier needed
+      if (EXPL) {
+        uint64_t lo, hi;
+        ring_of(ro, R, base, lo, hi);
+        const uint64_t sz = hi - lo;
+        j = (int)floor_div((base - lo + 1) * (uint64_t)C - 1, sz, 1.0 / (double)sz);
+        chunk_end = lo + floor_div((uint64_t)(j + 1) * sz, (uint64_t)C, dc.inv_C);
+      } else {
+        locate(base, n, R, C, dc, j, chunk_end);   // wave-uniform, no barrier needed
+      }
       if (last < chunk_end) {                    // chunk_end <= n: the tile is whole and inside one chunk
         tile_fast<CT, HAS_GRAD>(tab, j, base, out, write_back, grad, gr, eta);
         return;
@@ -145,7 +170,7 @@ __global__ __launch_bounds__(kThreads) void average_kernel(RepTable tab, int Crt
   for (int k = threadIdx.x; k < kTile; k += kThreads) {
     const uint64_t i = base + k;
     if (i >= n) break;
-    const int je = chunk_of(i, n, R, C);
+    const int je = EXPL ? chunk_of_v(ro, R, i, C) : chunk_of(i, n, R, C);
     const float m = elem_mean(tab, C, je, i, HAS_GRAD ? grad : nullptr, gr, eta);
     if (out != nullptr) out[i] = m;
     if (write_back)
@@ -155,22 +180,23 @@ __global__ __launch_bounds__(kThreads) void average_kernel(RepTable tab, int Crt
 
 template <int CT>
 void launch(const RepTable& tab, int C, uint64_t n, int R, float* out, int wb, const float* grad,
-            int gr, float eta, int aligned, hipStream_t st) {
+            int gr, float eta, int aligned, const RingOffsets* ro, hipStream_t st) {
   const unsigned blocks = (unsigned)((n + kTile - 1) / kTile);
   const DivConsts dc{1.0 / (double)n, 1.0 / (double)R, 1.0 / (double)C};
-  if (grad)
-    hipLaunchKernelGGL((average_kernel<CT, true>), dim3(blocks), dim3(kThreads), 0, st, tab, C, n, R,
-                       out, wb, grad, gr, eta, aligned, dc);
-  else
-    hipLaunchKernelGGL((average_kernel<CT, false>), dim3(blocks), dim3(kThreads), 0, st, tab, C, n, R,
-                       out, wb, grad, gr, eta, aligned, dc);
+  static const RingOffsets none = {};
+#define RV_AVG_LAUNCH(G, E)                                                                              \
+  hipLaunchKernelGGL((average_kernel<CT, G, E>), dim3(blocks), dim3(kThreads), 0, st, tab, C, n, R, out, \
+                     wb, grad, gr, eta, aligned, dc, E ? *ro : none)
+  if (ro) { if (grad) RV_AVG_LAUNCH(true, true); else RV_AVG_LAUNCH(false, true); }
+  else    { if (grad) RV_AVG_LAUNCH(true, false); else RV_AVG_LAUNCH(false, false); }
+#undef RV_AVG_LAUNCH
 }
 
 }  // namespace
 
-extern "C" rv_status rv_cluster_average(float* const* replicas, int C, size_t n, int R,
-                                        float* mean_out, int write_back, const float* grad,
-                                        int grad_replica, float eta, void* stream) {
+static rv_status average_impl(float* const* replicas, int C, size_t n, int R, const RingOffsets* ro,
+                              float* mean_out, int write_back, const float* grad, int grad_replica, float eta,
+                              void* stream) {
   if (replicas == nullptr || C < 1 || C > RV_MAX_C || R < 1 || R > RV_MAX_R || n == 0)
     return RV_E_INVAL;
   if (mean_out == nullptr && !write_back) return RV_E_INVAL;
@@ -192,13 +218,32 @@ extern "C" rv_status rv_cluster_average(float* const* replicas, int C, size_t n,
   hipStream_t st = (hipStream_t)stream;
   int wb = write_back ? 1 : 0;
   switch (C) {
-    case 1: launch<1>(tab, C, n, R, mean_out, wb, grad, grad_replica, eta, aligned, st); break;
-    case 2: launch<2>(tab, C, n, R, mean_out, wb, grad, grad_replica, eta, aligned, st); break;
-    case 3: launch<3>(tab, C, n, R, mean_out, wb, grad, grad_replica, eta, aligned, st); break;
-    case 4: launch<4>(tab, C, n, R, mean_out, wb, grad, grad_replica, eta, aligned, st); break;
-    case 8: launch<8>(tab, C, n, R, mean_out, wb, grad, grad_replica, eta, aligned, st); break;
-    case 16: launch<16>(tab, C, n, R, mean_out, wb, grad, grad_replica, eta, aligned, st); break;
-    default: launch<0>(tab, C, n, R, mean_out, wb, grad, grad_replica, eta, aligned, st); break;
+    case 1: launch<1>(tab, C, n, R, mean_out, wb, grad, grad_replica, eta, aligned, ro, st); break;
+    case 2: launch<2>(tab, C, n, R, mean_out, wb, grad, grad_replica, eta, aligned, ro, st); break;
+    case 3: launch<3>(tab, C, n, R, mean_out, wb, grad, grad_replica, eta, aligned, ro, st); break;
+    case 4: launch<4>(tab, C, n, R, mean_out, wb, grad, grad_replica, eta, aligned, ro, st); break;
+    case 8: launch<8>(tab, C, n, R, mean_out, wb, grad, grad_replica, eta, aligned, ro, st); break;
+    case 16: launch<16>(tab, C, n, R, mean_out, wb, grad, grad_replica, eta, aligned, ro, st); break;
+    default: launch<0>(tab, C, n, R, mean_out, wb, grad, grad_replica, eta, aligned, ro, st); break;
   }
   return rv_launch_status();
+}
+
+extern "C" rv_status rv_cluster_average(float* const* replicas, int C, size_t n, int R,
+                                        float* mean_out, int write_back, const float* grad,
+                                        int grad_replica, float eta, void* stream) {
+  return average_impl(replicas, C, n, R, nullptr, mean_out, write_back, grad, grad_replica, eta, stream);
+}
+
+extern "C" rv_status rv_cluster_average_v(float* const* replicas, int C, size_t n, const int64_t* ring_offsets,
+                                          int R, float* mean_out, int write_back, const float* grad,
+                                          int grad_replica, float eta, void* stream) {
+  if (ring_offsets == nullptr || R < 1 || R > RV_MAX_EXPLICIT_R) return RV_E_INVAL;
+  if (ring_offsets[0] != 0 || ring_offsets[R] != (int64_t)n) return RV_E_INVAL;
+  RingOffsets ro = {};
+  for (int r = 0; r <= R; ++r) {
+    if (r > 0 && ring_offsets[r] < ring_offsets[r - 1]) return RV_E_INVAL;
+    ro.off[r] = (uint64_t)ring_offsets[r];
+  }
+  return average_impl(replicas, C, n, R, &ro, mean_out, write_back, grad, grad_replica, eta, stream);
 }

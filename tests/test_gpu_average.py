@@ -111,3 +111,32 @@ def test_average_rejects_bad_arguments():
         rv.cluster_average([a, b], 1, mean_out=a)
     with pytest.raises(rv.RvError):
         rv.cluster_average([a, b], 1, mean_out=None, write_back=False)
+
+
+@pytest.mark.parametrize("C,offs", [
+    (4, [0, 10001, 10001, 30007, 50003]),           # unequal, unaligned boundaries, an empty ring
+    (16, [0, 4096, 12288, 40000]),
+    (3, [0, 1, 2, 3, 9999]),
+    (8, [0, 100000]),
+])
+def test_average_unequal_rings(C, offs):
+    import paper_2401_01728_amd as rv
+    n, R = offs[-1], len(offs) - 1
+    xs = _replicas(90 + C, C, n)
+    g = gen.normal_f32(90 + C, 99, n, std=1e-3)
+    dx = [dev(x) for x in xs]
+    out = torch.empty(n, dtype=torch.float32, device="cuda")
+    rv.cluster_average(dx, R, mean_out=out, grad=dev(g), grad_replica=C - 1, eta=0.5, ring_offsets=offs)
+    got = out.cpu().numpy()
+    assert np.array_equal(got, average.ring_order_mean_f32(xs, R, g, C - 1, 0.5, ring_offsets=offs))
+    ref = average.direct_mean(xs, g, C - 1, 0.5)
+    bound = 1e-6 * (np.mean(np.abs(np.stack(xs)).astype(np.float64), axis=0) + 0.5 * np.abs(g) / C)
+    assert np.all(np.abs(got.astype(np.float64) - ref) <= bound)
+    eq = [(r * n) // 4 for r in range(5)]                          # equal table == default partition
+    out2 = torch.empty(n, dtype=torch.float32, device="cuda"); out3 = torch.empty_like(out2)
+    rv.cluster_average(dx, 4, mean_out=out2, ring_offsets=eq)
+    rv.cluster_average(dx, 4, mean_out=out3)
+    assert torch.equal(out2, out3)
+    for bad in ([1, n], [0, n - 1], [0, 10, 5, n]):
+        with pytest.raises(rv.RvError):
+            rv.cluster_average(dx, len(bad) - 1, mean_out=out, ring_offsets=bad)

@@ -98,3 +98,26 @@ def test_fp32_ring_order_twin_matches_fp32_simulation_bitwise(C, R, n):
     ref = average.direct_mean(xs, g, 1 % C, 1e-2)
     bound = 1e-6 * (np.mean(np.abs(np.stack(xs)), axis=0) + 1e-2 * np.abs(g) / C)
     assert np.all(np.abs(twin.astype(np.float64) - ref) <= bound)
+
+
+@pytest.mark.parametrize("C", [2, 3, 4])
+def test_unequal_rings_equal_direct_mean(C):
+    """Rings of unequal size (explicit boundaries): still the plain mean, 2(C-1) rounds, and
+    the equal-split table reproduces the default partition."""
+    rng = np.random.default_rng(7 + C)
+    n = 61
+    for offs in ([0, 5, 5, 40, 61], [0, 1, 61], [0, 61], [0, 0, 30, 61], [0, 20, 41, 60, 61]):
+        R = len(offs) - 1
+        xs = [rng.integers(-50, 50, size=n).astype(np.float64) * C for _ in range(C)]
+        bufs, rounds, sent = average.multi_ring_allreduce(xs, R, ring_offsets=offs)
+        assert rounds == 2 * (C - 1)
+        ref = average.direct_mean(xs)
+        for b in bufs:
+            assert np.array_equal(b, ref)
+        flat = [x for rb in average.ring_partition(n, R, C, offs) for x in zip(rb[:-1], rb[1:])]
+        assert flat[0][0] == 0 and flat[-1][1] == n and all(a[1] == b[0] for a, b in zip(flat, flat[1:]))
+        x32 = [x.astype(np.float32) for x in xs]
+        b32, _, _ = average.multi_ring_allreduce(x32, R, dtype=np.float32, ring_offsets=offs)
+        assert np.array_equal(b32[0], average.ring_order_mean_f32(x32, R, ring_offsets=offs))
+    eq = [(r * n) // 4 for r in range(5)]
+    assert average.ring_partition(n, 4, C, eq) == average.ring_partition(n, 4, C)
