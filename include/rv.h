@@ -105,6 +105,15 @@ rv_status rv_stage_get_params(const rv_stage* s, float* flat_out, size_t n);
 rv_status rv_stage_last_grad(const rv_stage* s, float* flat_out, size_t n);
 
 /*
+ * Optional: the optimiser of the paper's single-cluster experiments (section 4.1, SGD
+ * with momentum and weight decay) in place of the plain step of Eq. 2:
+ *   d = g + weight_decay * w;  v <- momentum * v + d;  w <- w - eta * v
+ * Allocates the velocity buffer (fp32 [P]) on first use and zeroes it.  Only legal with no
+ * microbatch in flight.  momentum = weight_decay = 0 reproduces Eq. 2 exactly.
+ */
+rv_status rv_stage_set_optimizer(rv_stage* s, float momentum, float weight_decay);
+
+/*
  * Forward branch of Alg. 1: out = forward_pass(x_{c,p}, in) at the CURRENT
  * parameters.  Binds mb_id to a stash slot and to the current weight version.
  * in/out: device, MLP fp32 [microbatch, dims[0]] -> [microbatch, dims[n_layers]];
@@ -145,6 +154,10 @@ rv_status rv_stage_step(rv_stage* s, int64_t fwd_mb, const void* in, void* out, 
  */
 rv_status rv_block_update(float* w, const float* g, size_t n, float eta, void* bf16_out,
                           void* stream);
+
+/* The momentum / weight-decay step above on bare vectors; v (device [n]) is read and updated. */
+rv_status rv_block_update_momentum(float* w, const float* g, float* v, size_t n, float eta, float momentum,
+                                   float weight_decay, void* bf16_out, void* stream);
 
 /*
  * Arithmetic of one cycle of Parallel Multi-Ring All-Reduce (section 3.2) over C

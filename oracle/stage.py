@@ -31,7 +31,7 @@ class DuplicateMicrobatch(Exception):
 
 class Stage:
     def __init__(self, kind, tau, eta, flat_w, *, dims=None, n_blocks=None, d=None, h=None,
-                 f=None, eps=1e-5):
+                 f=None, eps=1e-5, momentum=0.0, weight_decay=0.0):
         assert kind in ("mlp", "decoder")
         self.kind, self.tau, self.eta = kind, int(tau), float(eta)
         self.dims, self.n_blocks, self.d, self.h, self.f, self.eps = dims, n_blocks, d, h, f, eps
@@ -40,6 +40,10 @@ class Stage:
         self.live = {}                                 # mb_id -> (w snapshot, input, k at forward)
         self.last_grad = None
         self.last_staleness = None
+        # optimiser of the paper's single-cluster experiments (section 4.1): SGD with
+        # momentum and weight decay; both zero = the plain step of Eq. 2
+        self.momentum, self.weight_decay = float(momentum), float(weight_decay)
+        self.v = np.zeros_like(self.w)
 
     def _f(self, w, x):
         if self.kind == "mlp":
@@ -66,7 +70,12 @@ class Stage:
             raise UnknownMicrobatch(mb_id)
         w_mb, x, k_fwd = self.live.pop(mb_id)
         dx, g = self._vjp(w_mb, x, np.array(dy, dtype=np.float64))
-        self.w = self.w - self.eta * g
+        if self.momentum == 0.0 and self.weight_decay == 0.0:
+            self.w = self.w - self.eta * g                      # Eq. 2
+        else:
+            d = g + self.weight_decay * self.w
+            self.v = self.momentum * self.v + d
+            self.w = self.w - self.eta * self.v
         self.last_grad = g
         self.last_staleness = self.k - k_fwd
         self.k += 1

@@ -24,12 +24,15 @@ SYMBOLS = {
     "rv_stage_num_params": (c_size_t, [c_void_p]),
     "rv_stage_in_flight": (c_int, [c_void_p]),
     "rv_stage_set_params": (c_int, [c_void_p, c_void_p, c_size_t]),
+    "rv_stage_set_optimizer": (c_int, [c_void_p, c_float, c_float]),
     "rv_stage_get_params": (c_int, [c_void_p, c_void_p, c_size_t]),
     "rv_stage_last_grad": (c_int, [c_void_p, c_void_p, c_size_t]),
     "rv_stage_forward": (c_int, [c_void_p, c_int64, c_void_p, c_void_p]),
     "rv_stage_backward": (c_int, [c_void_p, c_int64, c_void_p, c_void_p]),
     "rv_stage_step": (c_int, [c_void_p, c_int64, c_void_p, c_void_p, c_int64, c_void_p, c_void_p]),
     "rv_block_update": (c_int, [c_void_p, c_void_p, c_size_t, c_float, c_void_p, c_void_p]),
+    "rv_block_update_momentum": (c_int, [c_void_p, c_void_p, c_void_p, c_size_t, c_float, c_float, c_float, c_void_p,
+                                         c_void_p]),
     "rv_cluster_average": (c_int, [ctypes.POINTER(c_void_p), c_int, c_size_t, c_int, c_void_p, c_int,
                                    c_void_p, c_int, c_float, c_void_p]),
     "rv_cluster_average_v": (c_int, [ctypes.POINTER(c_void_p), c_int, c_size_t, ctypes.POINTER(c_int64), c_int,

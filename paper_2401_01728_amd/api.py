@@ -92,6 +92,9 @@ class Stage:
     def set_params(self, flat):
         _check(_lib.lib().rv_stage_set_params(self._h, _ptr(_dev_f32(flat)), flat.numel()))
 
+    def set_optimizer(self, momentum=0.0, weight_decay=0.0):
+        _check(_lib.lib().rv_stage_set_optimizer(self._h, momentum, weight_decay))
+
     def get_params(self, out=None):
         if out is None:
             out = torch.empty(self.num_params, dtype=torch.float32, device="cuda")
@@ -148,6 +151,13 @@ def block_update(w, g, eta, bf16_out=None, stream=None):
     if bf16_out is not None:
         assert bf16_out.is_cuda and bf16_out.dtype == torch.bfloat16 and bf16_out.numel() == w.numel()
     _check(_lib.lib().rv_block_update(_ptr(w), _ptr(g), w.numel(), eta, _ptr(bf16_out), _stream_handle(stream)))
+
+
+def block_update_momentum(w, g, v, eta, momentum, weight_decay, bf16_out=None, stream=None):
+    """rv_block_update_momentum: in-place momentum / weight-decay step on fp32 vectors."""
+    _dev_f32(w); _dev_f32(g, w.numel()); _dev_f32(v, w.numel())
+    _check(_lib.lib().rv_block_update_momentum(_ptr(w), _ptr(g), _ptr(v), w.numel(), eta, momentum, weight_decay,
+                                               _ptr(bf16_out), _stream_handle(stream)))
 
 
 def cluster_average(replicas, R, mean_out=None, write_back=False, grad=None, grad_replica=0, eta=0.0,

@@ -7,6 +7,8 @@
 // copy_kind: 0 none, 1 bf16 bits, 2 fp32
 rv_status rv_launch_update(float* w, const float* g, size_t n, float eta, void* copy, int copy_kind,
                            hipStream_t st);
+rv_status rv_launch_update_momentum(float* w, const float* g, float* v, size_t n, float eta, float mu, float wd,
+                                    void* copy, int copy_kind, hipStream_t st);
 rv_status rv_launch_publish(const float* w, size_t n, void* copy, int copy_kind, hipStream_t st);
 
 // ---- gemm_bf16.hip ----------------------------------------------------------------
@@ -66,6 +68,8 @@ struct rv_stage {
   size_t P = 0;
   float* master = nullptr;  // [P] fp32
   float* grad = nullptr;    // [P] fp32, gradient of the last backward
+  float* vel = nullptr;     // [P] fp32 momentum buffer (allocated by rv_stage_set_optimizer)
+  float momentum = 0.f, weight_decay = 0.f;
   size_t ver_elem = 0;      // bytes per parameter in a version slot (2 or 4)
   std::vector<char*> ver;   // tau+1 version slots
   std::vector<int> ver_ref; // in-flight microbatches bound to each slot

@@ -27,6 +27,7 @@ void free_all(rv_stage* s) {
   if (s->aux) (void)hipStreamDestroy(s->aux);
   if (s->master) (void)hipFree(s->master);
   if (s->grad) (void)hipFree(s->grad);
+  if (s->vel) (void)hipFree(s->vel);
   for (char* v : s->ver) if (v) (void)hipFree(v);
   if (s->stash) (void)hipFree(s->stash);
   if (s->work) (void)hipFree(s->work);
@@ -106,6 +107,17 @@ extern "C" rv_status rv_stage_set_params(rv_stage* s, const float* flat, size_t 
   return rv_launch_publish(s->master, s->P, s->ver[s->cur], copy_kind(s), s->st);
 }
 
+extern "C" rv_status rv_stage_set_optimizer(rv_stage* s, float momentum, float weight_decay) {
+  if (!s || !(momentum >= 0.f) || !(weight_decay >= 0.f)) return RV_E_INVAL;
+  if (rv_stage_in_flight(s) != 0) return RV_E_INVAL;
+  if (!s->vel) {
+    if (hipMalloc((void**)&s->vel, s->P * 4) != hipSuccess) { (void)hipGetLastError(); s->vel = nullptr; return RV_E_NOMEM; }
+  }
+  RV_HIP_TRY(hipMemsetAsync(s->vel, 0, s->P * 4, s->st));
+  s->momentum = momentum; s->weight_decay = weight_decay;
+  return RV_OK;
+}
+
 extern "C" rv_status rv_stage_get_params(const rv_stage* s, float* flat_out, size_t n) {
   if (!s || !flat_out || n != s->P) return RV_E_INVAL;
   RV_HIP_TRY(hipMemcpyAsync(flat_out, s->master, n * 4, hipMemcpyDeviceToDevice, s->st));
@@ -153,7 +165,9 @@ rv_status do_backward(rv_stage* s, int slot_i, const void* grad_out, void* grad_
   for (size_t v = 0; dst < 0 && v < s->ver.size(); ++v)
     if (s->ver_ref[v] == 0 && !(never_in_place && (int)v == s->cur)) dst = (int)v;
   if (dst < 0) return RV_E_DEVICE;  // unreachable by the counting argument above
-  rc = rv_launch_update(s->master, s->grad, s->P, s->eta, s->ver[dst], copy_kind(s), s->st);
+  rc = s->vel ? rv_launch_update_momentum(s->master, s->grad, s->vel, s->P, s->eta, s->momentum, s->weight_decay,
+                                          s->ver[dst], copy_kind(s), s->st)
+              : rv_launch_update(s->master, s->grad, s->P, s->eta, s->ver[dst], copy_kind(s), s->st);
   if (rc != RV_OK) return rc;
   s->cur = dst;
   return RV_OK;

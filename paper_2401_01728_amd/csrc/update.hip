@@ -62,6 +62,61 @@ __global__ __launch_bounds__(kThreads) void update_kernel(float* __restrict__ w,
   }
 }
 
+// The optimiser of the paper's single-cluster experiments (section 4.1: SGD with momentum
+// 0.9 and weight decay 5e-4) as a variant of the same update, in the usual form
+//   d = g + wd * w;   v <- mu * v + d;   w <- w - eta * v
+// (three fused multiply-adds per element; wd = mu = 0 gives Eq. 2 bit for bit).
+// 22 B/param with a bf16 copy: reads w, g, v, writes w, v, copy.
+template <int COPY>
+__global__ __launch_bounds__(kThreads) void update_momentum_kernel(float* __restrict__ w,
+                                                                   const float* __restrict__ g,
+                                                                   float* __restrict__ v, uint64_t n,
+                                                                   float eta, float mu, float wd,
+                                                                   void* __restrict__ copy, int aligned) {
+  const uint64_t base = (uint64_t)blockIdx.x * kTile;
+  auto step = [&](float wi, float gi, float& vi) {
+    const float d = __fmaf_rn(wd, wi, gi);
+    vi = __fmaf_rn(mu, vi, d);
+    return __fmaf_rn(-eta, vi, wi);
+  };
+  if (aligned && base + kTile <= n) {
+#pragma unroll
+    for (int u = 0; u < kVec; ++u) {
+      const uint64_t e = base + (uint64_t)(u * kThreads + threadIdx.x) * 4;
+      const f4 wv = *reinterpret_cast<const f4*>(w + e);
+      const f4 gv = __builtin_nontemporal_load(reinterpret_cast<const f4*>(g + e));
+      f4 vv = *reinterpret_cast<const f4*>(v + e);
+      f4 r;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        float vi = vv[c];
+        r[c] = step(wv[c], gv[c], vi);
+        vv[c] = vi;
+      }
+      *reinterpret_cast<f4*>(w + e) = r;
+      *reinterpret_cast<f4*>(v + e) = vv;
+      if (COPY == 1) {
+        u2 pk;
+        pk.x = rv_pack_bf16x2(r.x, r.y);
+        pk.y = rv_pack_bf16x2(r.z, r.w);
+        *reinterpret_cast<u2*>(reinterpret_cast<uint16_t*>(copy) + e) = pk;
+      } else if (COPY == 2) {
+        *reinterpret_cast<f4*>(reinterpret_cast<float*>(copy) + e) = r;
+      }
+    }
+    return;
+  }
+  for (int k = threadIdx.x; k < kTile; k += kThreads) {
+    const uint64_t i = base + k;
+    if (i >= n) break;
+    float vi = v[i];
+    const float r = step(w[i], g[i], vi);
+    w[i] = r; v[i] = vi;
+    if (COPY == 1) reinterpret_cast<uint16_t*>(copy)[i] = rv_f32_to_bf16(r);
+    if (COPY == 2) reinterpret_cast<float*>(copy)[i] = r;
+  }
+}
+
 // plain conversion of the master vector into a version slot (set_params)
 template <int COPY>
 __global__ __launch_bounds__(kThreads) void publish_kernel(const float* __restrict__ w, uint64_t n,
@@ -89,6 +144,21 @@ rv_status rv_launch_update(float* w, const float* g, size_t n, float eta, void* 
   return rv_launch_status();
 }
 
+rv_status rv_launch_update_momentum(float* w, const float* g, float* v, size_t n, float eta, float mu, float wd,
+                                    void* copy, int copy_kind, hipStream_t st) {
+  if (n == 0) return RV_OK;
+  int aligned = ((((uintptr_t)w) | ((uintptr_t)g) | ((uintptr_t)v)) & 15) == 0;
+  if (copy && (((uintptr_t)copy) & 15)) aligned = 0;
+  unsigned blocks = (unsigned)((n + kTile - 1) / kTile);
+  if (!copy || copy_kind == 0)
+    hipLaunchKernelGGL(update_momentum_kernel<0>, dim3(blocks), dim3(kThreads), 0, st, w, g, v, n, eta, mu, wd, nullptr, aligned);
+  else if (copy_kind == 1)
+    hipLaunchKernelGGL(update_momentum_kernel<1>, dim3(blocks), dim3(kThreads), 0, st, w, g, v, n, eta, mu, wd, copy, aligned);
+  else
+    hipLaunchKernelGGL(update_momentum_kernel<2>, dim3(blocks), dim3(kThreads), 0, st, w, g, v, n, eta, mu, wd, copy, aligned);
+  return rv_launch_status();
+}
+
 rv_status rv_launch_publish(const float* w, size_t n, void* copy, int copy_kind, hipStream_t st) {
   if (n == 0) return RV_OK;
   unsigned blocks = (unsigned)((n + kThreads - 1) / kThreads);
@@ -104,4 +174,13 @@ extern "C" rv_status rv_block_update(float* w, const float* g, size_t n, float e
   if (w == nullptr || g == nullptr || n == 0) return RV_E_INVAL;
   if ((const float*)w == g) return RV_E_INVAL;
   return rv_launch_update(w, g, n, eta, bf16_out, bf16_out ? 1 : 0, (hipStream_t)stream);
+}
+
+extern "C" rv_status rv_block_update_momentum(float* w, const float* g, float* v, size_t n, float eta,
+                                              float momentum, float weight_decay, void* bf16_out, void* stream) {
+  if (w == nullptr || g == nullptr || v == nullptr || n == 0) return RV_E_INVAL;
+  if ((const float*)w == g || (const float*)v == g || w == v) return RV_E_INVAL;
+  if (!(momentum >= 0.f) || !(weight_decay >= 0.f)) return RV_E_INVAL;
+  return rv_launch_update_momentum(w, g, v, n, eta, momentum, weight_decay, bf16_out, bf16_out ? 1 : 0,
+                                   (hipStream_t)stream);
 }

@@ -132,3 +132,24 @@ def test_error_paths_leave_state_unchanged():
     assert g.in_flight == 1
     g.backward(11, dy)
     assert g.in_flight == 0
+
+
+def test_stage_with_momentum_and_weight_decay():
+    """Stale-gradient schedule with the section 4.1 optimiser (momentum 0.9, weight decay 5e-4)."""
+    import paper_2401_01728_amd as rv
+    dims, mb, tau, eta = [33, 17, 9], 6, 2, 0.05
+    w0 = kaiming_uniform_flat(8, dims)
+    g = rv.Stage.mlp(dims, mb, tau, eta); g.set_params(dev(w0)); g.set_optimizer(0.9, 5e-4)
+    o = ostage.Stage("mlp", tau, eta, w0, dims=dims, momentum=0.9, weight_decay=5e-4)
+    n = 8
+    for t in range(n + tau):
+        if t < n:
+            x = gen.normal_f32(8, 10 + t, mb * dims[0]).reshape(mb, dims[0])
+            assert rel_l2(host64(g.forward(t, dev(x))), o.forward(t, x)) < 1e-5
+        j = t - tau
+        if j >= 0:
+            dy = gen.normal_f32(8, 50 + j, mb * dims[-1]).reshape(mb, dims[-1])
+            assert rel_l2(host64(g.backward(j, dev(dy))), o.backward(j, dy)) < 1e-5
+    assert rel_l2(host64(g.get_params()) - w0, o.w - w0) < 1e-4
+    with pytest.raises(rv.RvError):
+        g.set_optimizer(-1.0, 0.0)

@@ -39,3 +39,25 @@ def test_update_unaligned():
     ref = w.astype(np.float64) - 0.25 * g.astype(np.float64)
     assert np.all(np.abs(vw.cpu().numpy() - ref) <= 1e-6 * (np.abs(w) + 0.25 * np.abs(g)))
     assert bw[0].item() == 0 and bw[n + 1].item() == 0
+
+
+@pytest.mark.parametrize("n", [5, 2049, 1000003])
+def test_momentum_update(n):
+    """d = g + wd w; v <- mu v + d; w <- w - eta v (section 4.1 optimiser) vs fp64, 1e-6 bar."""
+    import paper_2401_01728_amd as rv
+    w = gen.normal_f32(13, 0, n, std=0.02); g = gen.normal_f32(13, 1, n, std=1e-3); v = gen.normal_f32(13, 2, n, std=1e-3)
+    eta, mu, wd = 0.01, 0.9, 5e-4
+    dw, dg, dv = dev(w), dev(g), dev(v)
+    copy = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    rv.block_update_momentum(dw, dg, dv, eta, mu, wd, bf16_out=copy)
+    f = lambda a: np.float64(np.float32(a))
+    v_ref = f(mu) * v.astype(np.float64) + (g.astype(np.float64) + f(wd) * w.astype(np.float64))
+    w_ref = w.astype(np.float64) - f(eta) * v_ref
+    gv, gw = dv.cpu().numpy(), dw.cpu().numpy()
+    assert np.all(np.abs(gv - v_ref) <= 1e-6 * (np.abs(v) + np.abs(g) + wd * np.abs(w)))
+    assert np.all(np.abs(gw - w_ref) <= 1e-6 * (np.abs(w) + eta * np.abs(v_ref)))
+    assert np.array_equal(copy.view(torch.int16).cpu().numpy().view(np.uint16), gen.f32_to_bf16_bits(gw))
+    # mu = wd = 0 is the plain step, bit for bit
+    a, b = dev(w), dev(w); z = torch.zeros(n, device="cuda")
+    rv.block_update_momentum(a, dg, z, eta, 0.0, 0.0); rv.block_update(b, dg, eta)
+    assert torch.equal(a, b)

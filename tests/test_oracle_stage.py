@@ -119,3 +119,39 @@ def test_decoder_stage_uses_forward_time_weights():
     _, g0 = blocks.decoder_backward(w0, L, d, h, f, 1e-5, x0, dy0)
     assert np.array_equal(dx1, ref_dx1) and st.last_staleness == 1
     assert np.allclose(st.w, w0 - 0.1 * g0 - 0.1 * g1, rtol=0, atol=1e-15)
+
+
+def test_momentum_weight_decay_closed_forms():
+    """Linear 1->1, x = 1, upstream gradient fixed at 1: dL/dw = dL/db = 1 every step."""
+    eta, mu, wd, n = 0.1, 0.9, 0.0, 6
+    st = stage.Stage("mlp", 0, eta, np.array([2.0, 1.0]), dims=[1, 1], momentum=mu, weight_decay=wd)
+    for t in range(n):
+        st.forward(t, np.array([[1.0]])); st.backward(t, np.array([[1.0]]))
+    # v_k = (1 - mu^k)/(1 - mu);  w_n = w_0 - eta * sum_{k=1..n} v_k
+    tot = sum((1 - mu ** k) / (1 - mu) for k in range(1, n + 1))
+    assert np.allclose(st.w, np.array([2.0, 1.0]) - eta * tot, rtol=0, atol=1e-14)
+    # weight decay alone with zero gradient: geometric shrink w_k = w_0 (1 - eta wd)^k
+    st = stage.Stage("mlp", 0, 0.1, np.array([2.0, -1.0]), dims=[1, 1], momentum=0.0, weight_decay=0.5)
+    for t in range(5):
+        st.forward(t, np.array([[0.0]])); st.backward(t, np.array([[0.0]]))
+    assert np.allclose(st.w, np.array([2.0, -1.0]) * (1 - 0.05) ** 5, rtol=0, atol=1e-15)
+    # both zero: the plain step of Eq. 2, bit for bit
+    a, b = _mlp_stage(1, 0.05, seed=4), _mlp_stage(1, 0.05, seed=4)
+    b.momentum = b.weight_decay = 0.0
+    rng = np.random.default_rng(0)
+    xs = [rng.normal(size=(5, 4)) for _ in range(4)]
+    _run_schedule(a, xs, lambda j, y: y, 1); _run_schedule(b, xs, lambda j, y: y, 1)
+    assert np.array_equal(a.w, b.w)
+
+
+def test_momentum_against_separate_loop():
+    rng = np.random.default_rng(21)
+    dims, eta, mu, wd = [4, 6, 3], 0.05, 0.9, 5e-4
+    st = stage.Stage("mlp", 0, eta, rng.normal(size=51) * 0.5, dims=dims, momentum=mu, weight_decay=wd)
+    w = st.w.copy(); v = np.zeros_like(w)
+    for t in range(5):
+        x = rng.normal(size=(5, 4)); dy = rng.normal(size=(5, 3))
+        st.forward(t, x); st.backward(t, dy)
+        _, g = blocks.mlp_backward(w, dims, x, dy)
+        v = mu * v + (g + wd * w); w = w - eta * v
+    assert np.allclose(st.w, w, rtol=0, atol=1e-15)
