@@ -23,7 +23,9 @@ struct DecPlan {
   // byte offsets inside one block's stash
   size_t s_x, s_m1, s_r1, s_u, s_qkv, s_a, s_lse, s_x1, s_m2, s_r2, s_v2, s_z, s_g, blk_bytes;
   // byte offsets inside the work buffer
-  size_t w_dres, w_dres16, w_dx1_16, w_dtmp, w_dz, w_dqkv, w_D, w_part, w_ytmp;
+  // (dy: three buffers, dx1 / dz / dqkv: two, so a block's weight-gradient products can run
+  // beside the next block)
+  size_t w_dres, w_dy[3], w_dx1_16[2], w_dtmp, w_dz[2], w_dqkv[2], w_D, w_part, w_ytmp;
 };
 
 }  // namespace
@@ -67,11 +69,11 @@ rv_status rv_dec_plan(rv_stage* s) {
   s->slot_bytes = b * p->L;
   size_t w = 0;
   p->w_dres = w; w += align_up(T * d * 4);
-  p->w_dres16 = w; w += align_up(T * d * 2);
-  p->w_dx1_16 = w; w += align_up(T * d * 2);
+  for (size_t& o : p->w_dy) { o = w; w += align_up(T * d * 2); }
+  for (size_t& o : p->w_dx1_16) { o = w; w += align_up(T * d * 2); }
   p->w_dtmp = w; w += align_up(T * d * 2);
-  p->w_dz = w; w += align_up(T * f * 2);
-  p->w_dqkv = w; w += align_up(T * 3 * d * 2);
+  for (size_t& o : p->w_dz) { o = w; w += align_up(T * f * 2); }
+  for (size_t& o : p->w_dqkv) { o = w; w += align_up(T * 3 * d * 2); }
   p->w_D = w; w += align_up(T * H * 4);
   const size_t part_ln = (size_t)rv_ln_bwd_parts(p->T) * 3 * d;
   const size_t part_cs = (size_t)rv_colsum_parts(p->T) * (size_t)std::max<int64_t>(3 * d, f);
@@ -146,11 +148,7 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
   hipStream_t st = s->st;
   const int T = p.T, d = p.d, f = p.f;
   float* dres = (float*)(s->work + p.w_dres);
-  uint16_t* dres16_buf = (uint16_t*)(s->work + p.w_dres16);   // bf16 dy of the block below
-  uint16_t* dx1_16 = (uint16_t*)(s->work + p.w_dx1_16);       // bf16 dx1 of the current block
   uint16_t* dtmp = (uint16_t*)(s->work + p.w_dtmp);
-  uint16_t* dz = (uint16_t*)(s->work + p.w_dz);
-  uint16_t* dqkv = (uint16_t*)(s->work + p.w_dqkv);
   float* Dbuf = (float*)(s->work + p.w_D);
   float* part = (float*)(s->work + p.w_part);
   const int ln_parts = rv_ln_bwd_parts(T), cs_parts = rv_colsum_parts(T);
@@ -163,7 +161,17 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
     RV_TRY(rv_colsum_bf16(dres16, d, T, d, part, st));
     RV_TRY(rv_reduce_rows(part, cs_parts, d, d, gl + p.b2, st));
   }
+  bool side = false;   // weight-gradient products on their own stream (decided at the first block)
   for (int l = p.L - 1; l >= 0; --l) {
+    // Buffers the weight-gradient products read alternate between blocks (dy: in threes, since
+    // block l-1 writes the dy of block l-2 while the products of block l still read theirs);
+    // block l may overwrite what the products of block l+2 read only after those are done.
+    const int par = l & 1;
+    if (side && l + 2 < p.L) RV_HIP_TRY(hipStreamWaitEvent(st, s->ev_wg_done[par], 0));
+    uint16_t* dx1_16 = (uint16_t*)(s->work + p.w_dx1_16[par]);   // bf16 dx1 of this block
+    uint16_t* dz = (uint16_t*)(s->work + p.w_dz[par]);
+    uint16_t* dqkv = (uint16_t*)(s->work + p.w_dqkv[par]);
+    uint16_t* dy_below = (uint16_t*)(s->work + p.w_dy[(l + 2) % 3]);   // = slot (l-1) mod 3
     const uint16_t* w = wv + (size_t)l * p.per_block;
     float* gl = s->grad + (size_t)l * p.per_block;
     const char* sb = slot.base + (size_t)l * p.blk_bytes;
@@ -176,9 +184,8 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
     const uint16_t* z = (const uint16_t*)(sb + p.s_z);
     const uint16_t* g = (const uint16_t*)(sb + p.s_g);
     // The four weight-gradient products of the block read only stashed activations and the
-    // bf16 gradients produced below; they are collected and issued as ONE grouped launch at
-    // the end of the block.  dy of this block must survive until then: the residual gradient
-    // in bf16 alternates between two buffers.
+    // bf16 gradients produced below; they are collected and issued as ONE grouped launch on
+    // the weight-gradient stream once the last of those gradients (dqkv) exists.
     rv_gemm_args wg[4];
     auto wgrad = [&](int k, const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb, int M, int N, float* out) {
       wg[k].A = A; wg[k].lda = lda; wg[k].a_kmajor = 1; wg[k].B = B; wg[k].ldb = ldb; wg[k].b_kmajor = 1;
@@ -204,11 +211,22 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
     RV_TRY(gemm(st, dres16, d, 0, w + p.wo, d, 0, T, d, d, RV_EPI_BF16, dtmp, d));                   // da = dx1 Wo^T
     RV_TRY(rv_attn_bwd(qkv, a, dtmp, (const float*)(sb + p.s_lse), Dbuf, dqkv, p.mb, p.S, d, p.H, st));
     wgrad(3, u, d, dqkv, 3 * d, d, 3 * d, gl + p.wqkv);                                              // dWqkv = u^T dqkv
-    RV_TRY(rv_gemm_wgrad_grouped(wg, 4, st));
+    // Measured: beside the next block's chain the products gain when they are at most two
+    // rounds of the chip's 512 workgroup slots (config 2: 768 tiles, step -4.5 %); larger ones
+    // fill the chip alone and only disturb the neighbours' caches (configs 3 and 5: +2 %).
+    side = rv_gemm_wgrad_grouped_tiles(wg, 4) <= 1024;
+    if (side) {
+      RV_HIP_TRY(hipEventRecord(s->ev_wg_ready, st));
+      RV_HIP_TRY(hipStreamWaitEvent(s->wgs, s->ev_wg_ready, 0));
+      RV_TRY(rv_gemm_wgrad_grouped(wg, 4, s->wgs));
+      RV_HIP_TRY(hipEventRecord(s->ev_wg_done[par], s->wgs));
+    } else {
+      RV_TRY(rv_gemm_wgrad_grouped(wg, 4, st));
+    }
     RV_TRY(rv_colsum_bf16(dqkv, 3 * d, T, 3 * d, part, st));
     RV_TRY(rv_reduce_rows(part, cs_parts, 3 * d, 3 * d, gl + p.bqkv, st));
     RV_TRY(gemm(st, dqkv, 3 * d, 0, w + p.wqkv, 3 * d, 0, T, d, 3 * d, RV_EPI_BF16, dtmp, d));       // du
-    uint16_t* dx16 = l == 0 ? (uint16_t*)grad_in : dres16_buf;
+    uint16_t* dx16 = l == 0 ? (uint16_t*)grad_in : dy_below;
     RV_TRY(rv_ln_bwd(dtmp, x, (const float*)(sb + p.s_m1), (const float*)(sb + p.s_r1), w + p.ln1g, dres, dres, dx16,
                      part, T, d, st));
     {
@@ -217,7 +235,12 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
       float* dst[3] = {gl + p.ln1g, gl + p.ln1b, l > 0 ? s->grad + (size_t)(l - 1) * p.per_block + p.b2 : nullptr};
       RV_TRY(rv_reduce_rows_multi(src, dst, l > 0 ? 3 : 2, ln_parts, 3 * (int64_t)d, d, st));
     }
-    dres16 = dres16_buf;             // dy of the block below
+    dres16 = dy_below;               // dy of the block below
+  }
+  // the caller's stream (and with it the update) continues behind the last products
+  if (side) {
+    RV_HIP_TRY(hipStreamWaitEvent(st, s->ev_wg_done[0], 0));
+    if (p.L > 1) RV_HIP_TRY(hipStreamWaitEvent(st, s->ev_wg_done[1], 0));
   }
   return RV_OK;
 }

@@ -712,6 +712,12 @@ rv_status rv_gemm_bf16(const rv_gemm_args& g, hipStream_t st) {
   return RV_E_INVAL;
 }
 
+int rv_gemm_wgrad_grouped_tiles(const rv_gemm_args* gs, int count) {
+  int tiles = 0;
+  for (int k = 0; k < count; ++k) tiles += ((gs[k].M + 127) / 128) * ((gs[k].N + 127) / 128);
+  return tiles;
+}
+
 rv_status rv_gemm_wgrad_grouped(const rv_gemm_args* gs, int count, hipStream_t st) {
   if (!gs || count < 1 || count > RV_GEMM_GROUP_MAX) return RV_E_INVAL;
   constexpr int BM = 128, BN = 128, BK = 64, NS = 2;

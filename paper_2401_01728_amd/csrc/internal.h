@@ -28,6 +28,8 @@ struct rv_gemm_args {
 rv_status rv_gemm_bf16(const rv_gemm_args& g, hipStream_t st);
 // up to RV_GEMM_GROUP_MAX weight-gradient products (both operands k-major, fp32 output) in one launch
 #define RV_GEMM_GROUP_MAX 4
+// workgroups (128x128 tiles) the grouped launch below would have
+int rv_gemm_wgrad_grouped_tiles(const rv_gemm_args* gs, int count);
 rv_status rv_gemm_wgrad_grouped(const rv_gemm_args* gs, int count, hipStream_t st);
 
 // ---- norm.hip ---------------------------------------------------------------------
@@ -65,6 +67,10 @@ struct rv_stage {
   hipStream_t st = nullptr;   // stream the next kernel is enqueued on (the caller's, or aux inside a step)
   hipStream_t aux = nullptr;  // second stream for the backward half of rv_stage_step
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  // third stream: the weight-gradient products of a decoder block run beside the next block's
+  // input-gradient chain
+  hipStream_t wgs = nullptr;
+  hipEvent_t ev_wg_ready = nullptr, ev_wg_done[2] = {nullptr, nullptr};
   size_t P = 0;
   float* master = nullptr;  // [P] fp32
   float* grad = nullptr;    // [P] fp32, gradient of the last backward

@@ -25,6 +25,9 @@ void free_all(rv_stage* s) {
   if (s->ev_fork) (void)hipEventDestroy(s->ev_fork);
   if (s->ev_join) (void)hipEventDestroy(s->ev_join);
   if (s->aux) (void)hipStreamDestroy(s->aux);
+  if (s->ev_wg_ready) (void)hipEventDestroy(s->ev_wg_ready);
+  for (hipEvent_t ev : s->ev_wg_done) if (ev) (void)hipEventDestroy(ev);
+  if (s->wgs) (void)hipStreamDestroy(s->wgs);
   if (s->master) (void)hipFree(s->master);
   if (s->grad) (void)hipFree(s->grad);
   if (s->vel) (void)hipFree(s->vel);
@@ -75,7 +78,11 @@ extern "C" rv_status rv_stage_create(const rv_stage_desc* d, rv_stage** out) {
   }
   if (hipStreamCreateWithFlags(&s->aux, hipStreamNonBlocking) != hipSuccess ||
       hipEventCreateWithFlags(&s->ev_fork, hipEventDisableTiming) != hipSuccess ||
-      hipEventCreateWithFlags(&s->ev_join, hipEventDisableTiming) != hipSuccess) {
+      hipEventCreateWithFlags(&s->ev_join, hipEventDisableTiming) != hipSuccess ||
+      hipStreamCreateWithFlags(&s->wgs, hipStreamNonBlocking) != hipSuccess ||
+      hipEventCreateWithFlags(&s->ev_wg_ready, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&s->ev_wg_done[0], hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&s->ev_wg_done[1], hipEventDisableTiming) != hipSuccess) {
     free_all(s); return RV_E_DEVICE;
   }
   s->cur = 0;
@@ -87,6 +94,7 @@ extern "C" rv_status rv_stage_destroy(rv_stage* s) {
   if (!s) return RV_E_INVAL;
   (void)hipStreamSynchronize(s->st);
   if (s->aux) (void)hipStreamSynchronize(s->aux);
+  if (s->wgs) (void)hipStreamSynchronize(s->wgs);
   free_all(s);
   return RV_OK;
 }
