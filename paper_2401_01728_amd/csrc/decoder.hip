@@ -25,7 +25,7 @@ struct DecPlan {
   // byte offsets inside the work buffer
   // (dy: three buffers, dx1 / dz / dqkv: two, so a block's weight-gradient products can run
   // beside the next block)
-  size_t w_dres, w_dy[3], w_dx1_16[2], w_dtmp, w_dz[2], w_dqkv[2], w_D, w_part, w_ytmp;
+  size_t w_dres, w_dy[3], w_dx1_16[2], w_dtmp, w_dz[2], w_dqkv[2], w_D, w_part_ln[2][2], w_part_cs, w_ytmp;
 };
 
 }  // namespace
@@ -77,7 +77,9 @@ rv_status rv_dec_plan(rv_stage* s) {
   p->w_D = w; w += align_up(T * H * 4);
   const size_t part_ln = (size_t)rv_ln_bwd_parts(p->T) * 3 * d;
   const size_t part_cs = (size_t)rv_colsum_parts(p->T) * (size_t)std::max<int64_t>(3 * d, f);
-  p->w_part = w; w += align_up(std::max(part_ln, part_cs) * 4);
+  for (auto& pair : p->w_part_ln)
+    for (size_t& o : pair) { o = w; w += align_up(part_ln * 4); }
+  p->w_part_cs = w; w += align_up(part_cs * 4);
   p->w_ytmp = w; w += align_up(T * d * 4);
   s->work_bytes = w;
   return RV_OK;
@@ -150,28 +152,46 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
   float* dres = (float*)(s->work + p.w_dres);
   uint16_t* dtmp = (uint16_t*)(s->work + p.w_dtmp);
   float* Dbuf = (float*)(s->work + p.w_D);
-  float* part = (float*)(s->work + p.w_part);
+  float* part_cs = (float*)(s->work + p.w_part_cs);
   const int ln_parts = rv_ln_bwd_parts(T), cs_parts = rv_colsum_parts(T);
+
+  // Everything that only feeds the parameter gradient - the four weight-gradient products of a
+  // block and the reductions behind the bias and LayerNorm gradients - is side work: nothing
+  // in the chain dy -> dx that the block below waits for reads it.  When the products are
+  // at most two rounds of the chip's 512 workgroup slots they go to a stream of their own and
+  // run beside the next block's chain (measured, config 2: step -4.5 %); larger ones fill the
+  // chip alone and only disturb the neighbours' caches (configs 3 and 5: +2 %), so there the
+  // side work stays in line.  Buffers that side work reads alternate between blocks (dy: in threes, since
+  // block l-1 writes the dy of block l-2 while the side work of block l still reads its own).
+  const int t128d = (d + 127) / 128, t128f = (f + 127) / 128, t128q = (3 * d + 127) / 128;
+  const bool side = 2 * t128d * t128f + t128d * t128d + t128d * t128q <= 1024;
+  hipStream_t ws = side ? s->wgs : st;
+  auto side_begin = [&]() -> rv_status {
+    if (!side) return RV_OK;
+    RV_HIP_TRY(hipEventRecord(s->ev_wg_ready, st));
+    RV_HIP_TRY(hipStreamWaitEvent(ws, s->ev_wg_ready, 0));
+    return RV_OK;
+  };
 
   // gradient of the last block's output: fp32 copy for the residual path, bf16 as operand
   RV_TRY(rv_bf16_to_f32((const uint16_t*)grad_out, dres, (int64_t)T * d, st));
   const uint16_t* dres16 = (const uint16_t*)grad_out;
   {
     float* gl = s->grad + (size_t)(p.L - 1) * p.per_block;
-    RV_TRY(rv_colsum_bf16(dres16, d, T, d, part, st));
-    RV_TRY(rv_reduce_rows(part, cs_parts, d, d, gl + p.b2, st));
+    RV_TRY(side_begin());
+    RV_TRY(rv_colsum_bf16(dres16, d, T, d, part_cs, ws));
+    RV_TRY(rv_reduce_rows(part_cs, cs_parts, d, d, gl + p.b2, ws));
   }
-  bool side = false;   // weight-gradient products on their own stream (decided at the first block)
   for (int l = p.L - 1; l >= 0; --l) {
-    // Buffers the weight-gradient products read alternate between blocks (dy: in threes, since
-    // block l-1 writes the dy of block l-2 while the products of block l still read theirs);
-    // block l may overwrite what the products of block l+2 read only after those are done.
     const int par = l & 1;
+    // block l may overwrite what the side work of block l+2 read only after that is done
     if (side && l + 2 < p.L) RV_HIP_TRY(hipStreamWaitEvent(st, s->ev_wg_done[par], 0));
     uint16_t* dx1_16 = (uint16_t*)(s->work + p.w_dx1_16[par]);   // bf16 dx1 of this block
     uint16_t* dz = (uint16_t*)(s->work + p.w_dz[par]);
     uint16_t* dqkv = (uint16_t*)(s->work + p.w_dqkv[par]);
     uint16_t* dy_below = (uint16_t*)(s->work + p.w_dy[(l + 2) % 3]);   // = slot (l-1) mod 3
+    float* part2 = (float*)(s->work + p.w_part_ln[par][0]);      // LayerNorm 2 / 1 partial sums
+    float* part1 = (float*)(s->work + p.w_part_ln[par][1]);
     const uint16_t* w = wv + (size_t)l * p.per_block;
     float* gl = s->grad + (size_t)l * p.per_block;
     const char* sb = slot.base + (size_t)l * p.blk_bytes;
@@ -183,9 +203,6 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
     const uint16_t* v2 = (const uint16_t*)(sb + p.s_v2);
     const uint16_t* z = (const uint16_t*)(sb + p.s_z);
     const uint16_t* g = (const uint16_t*)(sb + p.s_g);
-    // The four weight-gradient products of the block read only stashed activations and the
-    // bf16 gradients produced below; they are collected and issued as ONE grouped launch on
-    // the weight-gradient stream once the last of those gradients (dqkv) exists.
     rv_gemm_args wg[4];
     auto wgrad = [&](int k, const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb, int M, int N, float* out) {
       wg[k].A = A; wg[k].lda = lda; wg[k].a_kmajor = 1; wg[k].B = B; wg[k].ldb = ldb; wg[k].b_kmajor = 1;
@@ -195,49 +212,42 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
     wgrad(0, g, f, dres16, d, f, d, gl + p.w2);                                                      // dW2 = g^T dy
     RV_TRY(gemm(st, dres16, d, 0, w + p.w2, d, 0, T, f, d, RV_EPI_BF16_DGELU, dz, f, nullptr, nullptr, nullptr, z));
     wgrad(1, v2, d, dz, f, d, f, gl + p.w1);                                                         // dW1 = v2^T dz
-    RV_TRY(rv_colsum_bf16(dz, f, T, f, part, st));
-    RV_TRY(rv_reduce_rows(part, cs_parts, f, f, gl + p.b1, st));
+    RV_TRY(side_begin());
+    RV_TRY(rv_colsum_bf16(dz, f, T, f, part_cs, ws));
+    RV_TRY(rv_reduce_rows(part_cs, cs_parts, f, f, gl + p.b1, ws));
     RV_TRY(gemm(st, dz, f, 0, w + p.w1, f, 0, T, d, f, RV_EPI_BF16, dtmp, d));                       // dv2 = dz W1^T
     RV_TRY(rv_ln_bwd(dtmp, x1, (const float*)(sb + p.s_m2), (const float*)(sb + p.s_r2), w + p.ln2g, dres, dres,
-                     dx1_16, part, T, d, st));
-    dres16 = dx1_16;                 // (the dy buffer stays intact for dW2 in the grouped launch)
+                     dx1_16, part2, T, d, st));
     {
-      const float* src[3] = {part, part + d, part + 2 * d};
+      const float* src[3] = {part2, part2 + d, part2 + 2 * d};
       float* dst[3] = {gl + p.ln2g, gl + p.ln2b, gl + p.bo};                                         // dbo = sum dx1
-      RV_TRY(rv_reduce_rows_multi(src, dst, 3, ln_parts, 3 * (int64_t)d, d, st));
+      RV_TRY(side_begin());
+      RV_TRY(rv_reduce_rows_multi(src, dst, 3, ln_parts, 3 * (int64_t)d, d, ws));
     }
     // attention half
-    wgrad(2, a, d, dres16, d, d, d, gl + p.wo);                                                      // dWo = a^T dx1
-    RV_TRY(gemm(st, dres16, d, 0, w + p.wo, d, 0, T, d, d, RV_EPI_BF16, dtmp, d));                   // da = dx1 Wo^T
+    wgrad(2, a, d, dx1_16, d, d, d, gl + p.wo);                                                      // dWo = a^T dx1
+    RV_TRY(gemm(st, dx1_16, d, 0, w + p.wo, d, 0, T, d, d, RV_EPI_BF16, dtmp, d));                   // da = dx1 Wo^T
     RV_TRY(rv_attn_bwd(qkv, a, dtmp, (const float*)(sb + p.s_lse), Dbuf, dqkv, p.mb, p.S, d, p.H, st));
     wgrad(3, u, d, dqkv, 3 * d, d, 3 * d, gl + p.wqkv);                                              // dWqkv = u^T dqkv
-    // Measured: beside the next block's chain the products gain when they are at most two
-    // rounds of the chip's 512 workgroup slots (config 2: 768 tiles, step -4.5 %); larger ones
-    // fill the chip alone and only disturb the neighbours' caches (configs 3 and 5: +2 %).
-    side = rv_gemm_wgrad_grouped_tiles(wg, 4) <= 1024;
-    if (side) {
-      RV_HIP_TRY(hipEventRecord(s->ev_wg_ready, st));
-      RV_HIP_TRY(hipStreamWaitEvent(s->wgs, s->ev_wg_ready, 0));
-      RV_TRY(rv_gemm_wgrad_grouped(wg, 4, s->wgs));
-      RV_HIP_TRY(hipEventRecord(s->ev_wg_done[par], s->wgs));
-    } else {
-      RV_TRY(rv_gemm_wgrad_grouped(wg, 4, st));
-    }
-    RV_TRY(rv_colsum_bf16(dqkv, 3 * d, T, 3 * d, part, st));
-    RV_TRY(rv_reduce_rows(part, cs_parts, 3 * d, 3 * d, gl + p.bqkv, st));
+    RV_TRY(side_begin());
+    RV_TRY(rv_gemm_wgrad_grouped(wg, 4, ws));
+    RV_TRY(rv_colsum_bf16(dqkv, 3 * d, T, 3 * d, part_cs, ws));
+    RV_TRY(rv_reduce_rows(part_cs, cs_parts, 3 * d, 3 * d, gl + p.bqkv, ws));
     RV_TRY(gemm(st, dqkv, 3 * d, 0, w + p.wqkv, 3 * d, 0, T, d, 3 * d, RV_EPI_BF16, dtmp, d));       // du
     uint16_t* dx16 = l == 0 ? (uint16_t*)grad_in : dy_below;
     RV_TRY(rv_ln_bwd(dtmp, x, (const float*)(sb + p.s_m1), (const float*)(sb + p.s_r1), w + p.ln1g, dres, dres, dx16,
-                     part, T, d, st));
+                     part1, T, d, st));
     {
       // the residual gradient leaving this block is dy of the block below: its b2 gradient
-      const float* src[3] = {part, part + d, part + 2 * d};
+      const float* src[3] = {part1, part1 + d, part1 + 2 * d};
       float* dst[3] = {gl + p.ln1g, gl + p.ln1b, l > 0 ? s->grad + (size_t)(l - 1) * p.per_block + p.b2 : nullptr};
-      RV_TRY(rv_reduce_rows_multi(src, dst, l > 0 ? 3 : 2, ln_parts, 3 * (int64_t)d, d, st));
+      RV_TRY(side_begin());
+      RV_TRY(rv_reduce_rows_multi(src, dst, l > 0 ? 3 : 2, ln_parts, 3 * (int64_t)d, d, ws));
     }
+    if (side) RV_HIP_TRY(hipEventRecord(s->ev_wg_done[par], ws));
     dres16 = dy_below;               // dy of the block below
   }
-  // the caller's stream (and with it the update) continues behind the last products
+  // the caller's stream (and with it the update) continues behind the last side work
   if (side) {
     RV_HIP_TRY(hipStreamWaitEvent(st, s->ev_wg_done[0], 0));
     if (p.L > 1) RV_HIP_TRY(hipStreamWaitEvent(st, s->ev_wg_done[1], 0));
