@@ -244,6 +244,9 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
       RV_TRY(side_begin());
       RV_TRY(rv_reduce_rows_multi(src, dst, l > 0 ? 3 : 2, ln_parts, 3 * (int64_t)d, d, ws));
     }
+    // every gradient of block l is complete behind this point of `ws` (its b2 gradient came
+    // from the block above): the delayed update of the block follows at once
+    RV_TRY(rv_stage_update_range(s, (size_t)l * p.per_block, p.per_block, ws));
     if (side) RV_HIP_TRY(hipEventRecord(s->ev_wg_done[par], ws));
     dres16 = dy_below;               // dy of the block below
   }

@@ -28,6 +28,7 @@ struct rv_gemm_args {
 rv_status rv_gemm_bf16(const rv_gemm_args& g, hipStream_t st);
 // up to RV_GEMM_GROUP_MAX weight-gradient products (both operands k-major, fp32 output) in one launch
 #define RV_GEMM_GROUP_MAX 4
+rv_status rv_stage_update_range(rv_stage* s, size_t off, size_t n, hipStream_t st);
 // workgroups (128x128 tiles) the grouped launch below would have
 int rv_gemm_wgrad_grouped_tiles(const rv_gemm_args* gs, int count);
 rv_status rv_gemm_wgrad_grouped(const rv_gemm_args* gs, int count, hipStream_t st);
@@ -69,6 +70,7 @@ struct rv_stage {
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   // third stream: the weight-gradient products of a decoder block run beside the next block's
   // input-gradient chain
+  int upd_dst = -1;           // version slot the running backward publishes into
   hipStream_t wgs = nullptr;
   hipEvent_t ev_wg_ready = nullptr, ev_wg_done[2] = {nullptr, nullptr};
   size_t P = 0;

@@ -138,6 +138,17 @@ extern "C" rv_status rv_stage_last_grad(const rv_stage* s, float* flat_out, size
   return RV_OK;
 }
 
+// delayed update (Eq. 2, or its momentum / weight-decay variant) of parameters [off, off+n)
+// into the version slot chosen for this backward
+rv_status rv_stage_update_range(rv_stage* s, size_t off, size_t n, hipStream_t st) {
+  const int kind = s->dtype == RV_BF16 ? 1 : 2;
+  void* copy = (char*)s->ver[s->upd_dst] + off * s->ver_elem;
+  if (s->vel)
+    return rv_launch_update_momentum(s->master + off, s->grad + off, s->vel + off, n, s->eta, s->momentum,
+                                     s->weight_decay, copy, kind, st);
+  return rv_launch_update(s->master + off, s->grad + off, n, s->eta, copy, kind, st);
+}
+
 namespace {
 
 // forward branch: bind to a free slot and the newest version, enqueue on s->st
@@ -159,24 +170,30 @@ rv_status do_forward(rv_stage* s, int64_t mb_id, const void* in, void* out) {
 // overwrite the current version (a forward may be reading it on another stream).
 rv_status do_backward(rv_stage* s, int slot_i, const void* grad_out, void* grad_in, bool never_in_place) {
   rv_slot& sl = s->slots[slot_i];
-  rv_status rc = s->kind == RV_MLP ? rv_mlp_backward(s, sl, grad_out, grad_in)
-                                   : rv_dec_backward(s, sl, grad_out, grad_in);
-  if (rc != RV_OK) return rc;
-  // retire the microbatch, then publish the updated block as a new version in a slot that
-  // no in-flight microbatch is bound to (with tau+1 slots and at most tau left in flight
-  // there is always one; the current slot itself if nobody refers to it).
+  // The updated block is published as a new version in a slot that no in-flight microbatch
+  // will be bound to once this one has retired (with tau+1 slots and at most tau left in
+  // flight there is always one; the current slot itself if nobody else refers to it).  The
+  // slot is chosen before the backward so that a stage kind may update layer by layer as the
+  // gradients complete; a layer's weights are not read again once its gradient exists, so
+  // this is safe even when the slot is the one this backward reads.
+  int dst = -1;
+  auto refs = [&](size_t v) { return s->ver_ref[v] - ((int)v == sl.ver ? 1 : 0); };
+  if (!never_in_place && refs(s->cur) == 0) dst = s->cur;
+  for (size_t v = 0; dst < 0 && v < s->ver.size(); ++v)
+    if (refs(v) == 0 && !(never_in_place && (int)v == s->cur)) dst = (int)v;
+  if (dst < 0) return RV_E_DEVICE;  // unreachable by the counting argument above
+  s->upd_dst = dst;
+  rv_status rc;
+  if (s->kind == RV_MLP) {
+    rc = rv_mlp_backward(s, sl, grad_out, grad_in);
+    if (rc == RV_OK) rc = rv_stage_update_range(s, 0, s->P, s->st);
+  } else {
+    rc = rv_dec_backward(s, sl, grad_out, grad_in);   // updates block by block
+  }
+  if (rc != RV_OK) return rc;   // (a failed launch leaves the stage unusable)
   sl.live = false;
   s->ver_ref[sl.ver] -= 1;
   sl.ver = -1;
-  int dst = -1;
-  if (!never_in_place && s->ver_ref[s->cur] == 0) dst = s->cur;
-  for (size_t v = 0; dst < 0 && v < s->ver.size(); ++v)
-    if (s->ver_ref[v] == 0 && !(never_in_place && (int)v == s->cur)) dst = (int)v;
-  if (dst < 0) return RV_E_DEVICE;  // unreachable by the counting argument above
-  rc = s->vel ? rv_launch_update_momentum(s->master, s->grad, s->vel, s->P, s->eta, s->momentum, s->weight_decay,
-                                          s->ver[dst], copy_kind(s), s->st)
-              : rv_launch_update(s->master, s->grad, s->P, s->eta, s->ver[dst], copy_kind(s), s->st);
-  if (rc != RV_OK) return rc;
   s->cur = dst;
   return RV_OK;
 }
