@@ -133,6 +133,18 @@ __device__ __forceinline__ void store_owned(const f32x16* acc, float mul, uint16
     }
 }
 
+// Workgroup -> (row block, head, sequence).  Causal work per row block is a ramp, and
+// consecutive workgroup ids go to the 8 XCDs in turn: the block index must be the SLOWEST
+// digit of the id, or whole XCDs get only long (or only short) blocks and the kernel lasts as
+// long as the unluckiest XCD (measured: 1.2x - 1.7x).  rank 0 is the heaviest block, so the
+// long blocks also start first.
+__device__ __forceinline__ void attn_block(int H, int nseq, int& rank, int& h, int& b) {
+  const int per = H * nseq;
+  rank = blockIdx.x / per;
+  const int rest = blockIdx.x % per;
+  h = rest % H; b = rest / H;
+}
+
 // ----------------------------------------------------------------------------------------
 // forward
 // ----------------------------------------------------------------------------------------
@@ -140,11 +152,13 @@ template <int DH>
 __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(const uint16_t* __restrict__ qkv, int64_t ld,
                                                             uint16_t* __restrict__ out, int64_t ldo,
                                                             float* __restrict__ lse2, int S, int d, int H,
-                                                            float c2) {
+                                                            int nseq, float c2) {
   extern __shared__ __align__(16) char smem[];
   constexpr int BUF = L<DH>::KC_BYTES + L<DH>::KM_BYTES;   // K tile (k-contiguous) + V tile (transpose-read)
-  const int qb = gridDim.x - 1 - blockIdx.x;               // long rows first
-  const int h = blockIdx.y, b = blockIdx.z;
+  const int nblk = (S + BROWS - 1) / BROWS;
+  int rank, h, b;
+  attn_block(H, nseq, rank, h, b);
+  const int qb = nblk - 1 - rank;                          // long rows first
   const int wave = threadIdx.x >> 6, l = threadIdx.x & 63, grp = l >> 5;
   const int q0 = qb * BROWS + wave * WROWS;
   const bool active = q0 < S;
@@ -268,7 +282,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kv_kernel(const uint16_t* _
                                                                const float* __restrict__ lse2,
                                                                const float* __restrict__ Dv,
                                                                uint16_t* __restrict__ dqkv, int S, int d, int H,
-                                                               float c2, float scale) {
+                                                               int nseq, float c2, float scale) {
   extern __shared__ __align__(16) char smem[];
   char* Qkc = smem;                         // Q tile, k-contiguous (for S = Q K^T)
   char* Qkm = Qkc + L<DH>::KC_BYTES;        // Q tile, transpose-read (for dK^T = Q^T dS)
@@ -276,7 +290,8 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kv_kernel(const uint16_t* _
   char* Okm = Okc + L<DH>::KC_BYTES;        // dO tile, transpose-read (for dV^T = dO^T P)
   float* stat = reinterpret_cast<float*>(Okm + L<DH>::KM_BYTES);   // lse2[64], D[64]
 
-  const int jb = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+  int jb, h, b;                             // the first key block sees every query: heaviest
+  attn_block(H, nseq, jb, h, b);
   const int wave = threadIdx.x >> 6, l = threadIdx.x & 63, grp = l >> 5;
   const int j0 = jb * BROWS + wave * WROWS;
   const bool active = j0 < S;
@@ -356,14 +371,16 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_q_kernel(const uint16_t* __
                                                               const float* __restrict__ lse2,
                                                               const float* __restrict__ Dv,
                                                               uint16_t* __restrict__ dqkv, int S, int d, int H,
-                                                              float c2, float scale) {
+                                                              int nseq, float c2, float scale) {
   extern __shared__ __align__(16) char smem[];
   char* Kkc = smem;                         // K tile, k-contiguous (S^T = K Q^T)
   char* Kkm = Kkc + L<DH>::KC_BYTES;        // K tile, transpose-read (dQ^T = K^T dS^T)
   char* Vkc = Kkm + L<DH>::KM_BYTES;        // V tile, k-contiguous (dP^T = V dO^T)
 
-  const int qb = gridDim.x - 1 - blockIdx.x;
-  const int h = blockIdx.y, b = blockIdx.z;
+  const int nblk = (S + BROWS - 1) / BROWS;
+  int rank, h, b;
+  attn_block(H, nseq, rank, h, b);
+  const int qb = nblk - 1 - rank;
   const int wave = threadIdx.x >> 6, l = threadIdx.x & 63, grp = l >> 5;
   const int q0 = qb * BROWS + wave * WROWS;
   const bool active = q0 < S;
@@ -446,17 +463,18 @@ rv_status rv_attn_fwd(const uint16_t* qkv, uint16_t* out, float* lse2, int mb, i
   if (!qkv || !out || !lse2 || !shape_ok(mb, S, d, H)) return RV_E_INVAL;
   const int dh = d / H;
   const float c2 = 1.4426950408889634f / sqrtf((float)dh);
-  dim3 grid((S + BROWS - 1) / BROWS, H, mb);
+  const int nwg = ((S + BROWS - 1) / BROWS) * H * mb;
+  dim3 grid(nwg);
   if (dh == 64) {
     constexpr int smem = 2 * (L<64>::KC_BYTES + L<64>::KM_BYTES);
     RV_TRY(set_smem(attn_fwd_kernel<64>, smem));
     hipLaunchKernelGGL(attn_fwd_kernel<64>, grid, dim3(kThreads), smem, st, qkv, (int64_t)3 * d, out, (int64_t)d,
-                       lse2, S, d, H, c2);
+                       lse2, S, d, H, mb, c2);
   } else {
     constexpr int smem = 2 * (L<128>::KC_BYTES + L<128>::KM_BYTES);
     RV_TRY(set_smem(attn_fwd_kernel<128>, smem));
     hipLaunchKernelGGL(attn_fwd_kernel<128>, grid, dim3(kThreads), smem, st, qkv, (int64_t)3 * d, out,
-                       (int64_t)d, lse2, S, d, H, c2);
+                       (int64_t)d, lse2, S, d, H, mb, c2);
   }
   return rv_launch_status();
 }
@@ -468,7 +486,8 @@ rv_status rv_attn_bwd(const uint16_t* qkv, const uint16_t* out, const uint16_t* 
   const float scale = 1.0f / sqrtf((float)dh);
   const float c2 = 1.4426950408889634f * scale;
   const int64_t total = (int64_t)mb * S * H;
-  dim3 grid((S + BROWS - 1) / BROWS, H, mb);
+  const int nwg = ((S + BROWS - 1) / BROWS) * H * mb;
+  dim3 grid(nwg);
   const unsigned rd_blocks = (unsigned)((total * 8 + 255) / 256);
   if (dh == 64) {
     constexpr int s1 = 2 * (L<64>::KC_BYTES + L<64>::KM_BYTES) + 2 * TILE * 4;
@@ -476,18 +495,18 @@ rv_status rv_attn_bwd(const uint16_t* qkv, const uint16_t* out, const uint16_t* 
     RV_TRY(set_smem(attn_bwd_kv_kernel<64>, s1)); RV_TRY(set_smem(attn_bwd_q_kernel<64>, s2));
     hipLaunchKernelGGL(attn_rowdot_kernel<64>, dim3(rd_blocks), dim3(256), 0, st, out, dout, (int64_t)d, Dbuf, S, H, total);
     hipLaunchKernelGGL(attn_bwd_kv_kernel<64>, grid, dim3(kThreads), s1, st, qkv, (int64_t)3 * d, dout, (int64_t)d,
-                       lse2, Dbuf, dqkv, S, d, H, c2, scale);
+                       lse2, Dbuf, dqkv, S, d, H, mb, c2, scale);
     hipLaunchKernelGGL(attn_bwd_q_kernel<64>, grid, dim3(kThreads), s2, st, qkv, (int64_t)3 * d, dout, (int64_t)d,
-                       lse2, Dbuf, dqkv, S, d, H, c2, scale);
+                       lse2, Dbuf, dqkv, S, d, H, mb, c2, scale);
   } else {
     constexpr int s1 = 2 * (L<128>::KC_BYTES + L<128>::KM_BYTES) + 2 * TILE * 4;
     constexpr int s2 = 2 * L<128>::KC_BYTES + L<128>::KM_BYTES;
     RV_TRY(set_smem(attn_bwd_kv_kernel<128>, s1)); RV_TRY(set_smem(attn_bwd_q_kernel<128>, s2));
     hipLaunchKernelGGL(attn_rowdot_kernel<128>, dim3(rd_blocks), dim3(256), 0, st, out, dout, (int64_t)d, Dbuf, S, H, total);
     hipLaunchKernelGGL(attn_bwd_kv_kernel<128>, grid, dim3(kThreads), s1, st, qkv, (int64_t)3 * d, dout, (int64_t)d,
-                       lse2, Dbuf, dqkv, S, d, H, c2, scale);
+                       lse2, Dbuf, dqkv, S, d, H, mb, c2, scale);
     hipLaunchKernelGGL(attn_bwd_q_kernel<128>, grid, dim3(kThreads), s2, st, qkv, (int64_t)3 * d, dout, (int64_t)d,
-                       lse2, Dbuf, dqkv, S, d, H, c2, scale);
+                       lse2, Dbuf, dqkv, S, d, H, mb, c2, scale);
   }
   return rv_launch_status();
 }
