@@ -311,17 +311,29 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kv_kernel(const uint16_t* _
   for (int dt = 0; dt < DH / 32; ++dt) { dk[dt] = zero16(); dv[dt] = zero16(); }
   const int ji = j0 + (l & 31);
 
+  // The next tile's global loads are in flight while the current tile is computed; they are
+  // parked in LDS after the barrier that ends the compute phase.
   const int nit = S / TILE;
-  for (int it = jb * (BROWS / TILE); it < nit; ++it) {
+  const int it0 = jb * (BROWS / TILE);
+  u32x4 rq[L<DH>::CHUNKS], ro[L<DH>::CHUNKS];
+  float rstat = 0.f;
+  auto fetch = [&](int it) {
     const int i0 = it * TILE;
-    u32x4 r[L<DH>::CHUNKS];
-    g2r<DH>(r, Qg + (int64_t)i0 * ld, ld);
-    r2s<DH, L<DH>::PKC>(r, Qkc); r2s<DH, L<DH>::PKM>(r, Qkm);
-    g2r<DH>(r, Og + (int64_t)i0 * ldo, ldo);
-    r2s<DH, L<DH>::PKC>(r, Okc); r2s<DH, L<DH>::PKM>(r, Okm);
-    if (threadIdx.x < TILE) stat[threadIdx.x] = lse_g[i0 + threadIdx.x];
-    else if (threadIdx.x < 2 * TILE) stat[threadIdx.x] = D_g[i0 + threadIdx.x - TILE];
-    __syncthreads();
+    g2r<DH>(rq, Qg + (int64_t)i0 * ld, ld);
+    g2r<DH>(ro, Og + (int64_t)i0 * ldo, ldo);
+    if (threadIdx.x < TILE) rstat = lse_g[i0 + threadIdx.x];
+    else if (threadIdx.x < 2 * TILE) rstat = D_g[i0 + threadIdx.x - TILE];
+  };
+  auto park = [&]() {
+    r2s<DH, L<DH>::PKC>(rq, Qkc); r2s<DH, L<DH>::PKM>(rq, Qkm);
+    r2s<DH, L<DH>::PKC>(ro, Okc); r2s<DH, L<DH>::PKM>(ro, Okm);
+    if (threadIdx.x < 2 * TILE) stat[threadIdx.x] = rstat;
+  };
+  if (it0 < nit) { fetch(it0); park(); }
+  __syncthreads();
+  for (int it = it0; it < nit; ++it) {
+    const int i0 = it * TILE;
+    if (it + 1 < nit) fetch(it + 1);
     if (active) {
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub) {
@@ -355,6 +367,8 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kv_kernel(const uint16_t* _
         }
       }
     }
+    __syncthreads();           // everyone is done reading this tile
+    if (it + 1 < nit) park();
     __syncthreads();
   }
   if (!active) return;
@@ -402,14 +416,20 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_q_kernel(const uint16_t* __
   for (int dt = 0; dt < DH / 32; ++dt) dq[dt] = zero16();
 
   const int nkt = min(S, (qb + 1) * BROWS) / TILE;
+  u32x4 rk[L<DH>::CHUNKS], rv[L<DH>::CHUNKS];
+  auto fetch = [&](int kt) {
+    g2r<DH>(rk, Kg + (int64_t)kt * TILE * ld, ld);
+    g2r<DH>(rv, Vg + (int64_t)kt * TILE * ld, ld);
+  };
+  auto park = [&]() {
+    r2s<DH, L<DH>::PKC>(rk, Kkc); r2s<DH, L<DH>::PKM>(rk, Kkm);
+    r2s<DH, L<DH>::PKC>(rv, Vkc);
+  };
+  fetch(0); park();
+  __syncthreads();
   for (int kt = 0; kt < nkt; ++kt) {
     const int k0 = kt * TILE;
-    u32x4 r[L<DH>::CHUNKS];
-    g2r<DH>(r, Kg + (int64_t)k0 * ld, ld);
-    r2s<DH, L<DH>::PKC>(r, Kkc); r2s<DH, L<DH>::PKM>(r, Kkm);
-    g2r<DH>(r, Vg + (int64_t)k0 * ld, ld);
-    r2s<DH, L<DH>::PKC>(r, Vkc);
-    __syncthreads();
+    if (kt + 1 < nkt) fetch(kt + 1);
     if (active && k0 <= q0 + WROWS - 1) {
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub) {
@@ -438,6 +458,8 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_q_kernel(const uint16_t* __
         }
       }
     }
+    __syncthreads();           // everyone is done reading this tile
+    if (kt + 1 < nkt) park();
     __syncthreads();
   }
   if (!active) return;
