@@ -40,6 +40,18 @@ rv_status rv_k_gemm_bf16(const void* A, int64_t lda, int a_kmajor, const void* B
                          const void* zin, int tile, void* stream);
 
 /*
+ * Up to 4 weight-gradient products dW_i[M_i,N_i] = X_i^T dY_i (both operands k-major: X_i is
+ * [K, M_i] with pitch lda_i, dY_i is [K, N_i] with pitch ldb_i; fp32 outputs with pitch N_i)
+ * over the same K tokens, in ONE launch: the four products of a decoder block together fill
+ * the chip where each alone would not.  Arrays are HOST arrays of `count` entries; operand
+ * pointers are device pointers.  Same divisibility rules as rv_k_gemm_bf16; results equal
+ * rv_k_gemm_bf16(..., epilogue 5, tile 2128) bit for bit.
+ */
+rv_status rv_k_gemm_wgrad_grouped(int count, const void* const* X, const int64_t* lda, const void* const* dY,
+                                  const int64_t* ldb, const int* M, const int* N, int K, float* const* dW,
+                                  void* stream);
+
+/*
  * LayerNorm over the last dimension (biased variance, eps inside the root), affine in
  * bf16: y bf16 [T,d] = (x - mean) * rstd * gamma + beta; mean, rstd fp32 [T] are kept for
  * the backward.  x is fp32 [T,d], or bf16 when x_is_bf16 (then xcopy receives it widened

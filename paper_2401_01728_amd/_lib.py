@@ -42,6 +42,8 @@ SYMBOLS = {
 
 # per-kernel entry points declared in include/rv_kernels.h
 KERNEL_SYMBOLS = {
+    "rv_k_gemm_wgrad_grouped": (c_int, [c_int, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_void_p, c_int,
+                                        c_void_p, c_void_p]),
     "rv_k_gemm_bf16": (c_int, [c_void_p, c_int64, c_int, c_void_p, c_int64, c_int, c_int, c_int, c_int, c_int,
                                c_void_p, c_int64, c_void_p, c_void_p, c_void_p, c_int64, c_void_p, c_int,
                                c_void_p]),

@@ -762,3 +762,16 @@ extern "C" rv_status rv_k_gemm_bf16(const void* A, int64_t lda, int a_kmajor, co
   g.bias = (const uint16_t*)bias; g.resid = resid; g.ldr = ldr; g.zin = (const uint16_t*)zin; g.tile = tile;
   return rv_gemm_bf16(g, (hipStream_t)stream);
 }
+
+extern "C" rv_status rv_k_gemm_wgrad_grouped(int count, const void* const* X, const int64_t* lda,
+                                             const void* const* dY, const int64_t* ldb, const int* M, const int* N,
+                                             int K, float* const* dW, void* stream) {
+  if (count < 1 || count > RV_GEMM_GROUP_MAX || !X || !lda || !dY || !ldb || !M || !N || !dW) return RV_E_INVAL;
+  rv_gemm_args g[RV_GEMM_GROUP_MAX];
+  for (int k = 0; k < count; ++k) {
+    g[k].A = (const uint16_t*)X[k]; g[k].lda = lda[k]; g[k].a_kmajor = 1;
+    g[k].B = (const uint16_t*)dY[k]; g[k].ldb = ldb[k]; g[k].b_kmajor = 1;
+    g[k].M = M[k]; g[k].N = N[k]; g[k].K = K; g[k].epi = EPI_F32; g[k].out = dW[k]; g[k].ldo = N[k];
+  }
+  return rv_gemm_wgrad_grouped(g, count, (hipStream_t)stream);
+}

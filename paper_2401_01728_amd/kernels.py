@@ -19,6 +19,18 @@ def gemm_bf16(A, a_kmajor, B, b_kmajor, M, N, K, epilogue, out, out2=None, bias=
     return out
 
 
+def gemm_wgrad_grouped(xs, dys, outs, stream=None):
+    """rv_k_gemm_wgrad_grouped: outs[i] (fp32 [M_i, N_i]) = xs[i]^T @ dys[i]; xs[i] is [K, M_i], dys[i] is [K, N_i]."""
+    n = len(xs)
+    K = xs[0].shape[0]
+    vp = (ctypes.c_void_p * n); i64 = (ctypes.c_int64 * n); i32 = (ctypes.c_int * n)
+    X = vp(*[_ptr(x) for x in xs]); Y = vp(*[_ptr(y) for y in dys]); O = vp(*[_ptr(o) for o in outs])
+    lda = i64(*[x.stride(0) for x in xs]); ldb = i64(*[y.stride(0) for y in dys])
+    M = i32(*[x.shape[1] for x in xs]); N = i32(*[y.shape[1] for y in dys])
+    _check(_lib.lib().rv_k_gemm_wgrad_grouped(n, X, lda, Y, ldb, M, N, K, O, _stream_handle(stream)))
+    return outs
+
+
 def layernorm_fwd(x, gamma, beta, eps, xcopy=None, stream=None):
     T, d = x.shape
     y = torch.empty(T, d, dtype=torch.bfloat16, device="cuda")

@@ -92,3 +92,23 @@ def test_strided_operands_and_rejects():
         k.gemm_bf16(x, 0, w, 1, M, N, 100, k.EPI_BF16_BIAS, o, bias=b)       # K % 64
     with pytest.raises(rv.RvError):
         k.gemm_bf16(x, 1, w, 0, M, N, K, k.EPI_BF16, o)                      # unsupported layout pair
+
+
+def test_grouped_weight_gradient_products():
+    """Four products of different widths in one launch equal the single launches bit for bit."""
+    from paper_2401_01728_amd import kernels as k
+    K = 320
+    dims = [(192, 256), (64, 64), (136, 512), (512, 72)]
+    xs, dys, outs, refs = [], [], [], []
+    for i, (M, N) in enumerate(dims):
+        x, x64 = bf16_normal(9, 2 * i, (K, M)); dy, dy64 = bf16_normal(9, 2 * i + 1, (K, N), std=1e-2)
+        xs.append(x); dys.append(dy); outs.append(_out((M, N), torch.float32)); refs.append(x64.T @ dy64)
+    k.gemm_wgrad_grouped(xs, dys, outs)
+    for i, (M, N) in enumerate(dims):
+        assert rel_l2(host64(outs[i]), refs[i]) < 1e-5
+        single = _out((M, N), torch.float32)
+        k.gemm_bf16(xs[i], 1, dys[i], 1, M, N, K, k.EPI_F32, single, tile=2128)
+        assert torch.equal(single, outs[i])
+    import paper_2401_01728_amd as rv
+    with pytest.raises(rv.RvError):
+        k.gemm_wgrad_grouped(xs * 2, dys * 2, outs * 2)      # more than four
