@@ -45,7 +45,7 @@ rv_status rv_k_gemm_bf16(const void* A, int64_t lda, int a_kmajor, const void* B
  * over the same K tokens, in ONE launch: the four products of a decoder block together fill
  * the chip where each alone would not.  Arrays are HOST arrays of `count` entries; operand
  * pointers are device pointers.  Same divisibility rules as rv_k_gemm_bf16; results equal
- * rv_k_gemm_bf16(..., epilogue 5, tile 2128) bit for bit.
+ * rv_k_gemm_bf16(..., epilogue 5, tile 5256) bit for bit.
  */
 rv_status rv_k_gemm_wgrad_grouped(int count, const void* const* X, const int64_t* lda, const void* const* dY,
                                   const int64_t* ldb, const int* M, const int* N, int K, float* const* dW,

@@ -156,18 +156,14 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
   const int ln_parts = rv_ln_bwd_parts(T), cs_parts = rv_colsum_parts(T);
 
   // Everything that only feeds the parameter gradient - the four weight-gradient products of a
-  // block and the reductions behind the bias and LayerNorm gradients - is side work: nothing
-  // in the chain dy -> dx that the block below waits for reads it.  When the products are
-  // at most two rounds of the chip's 512 workgroup slots they go to a stream of their own and
-  // run beside the next block's chain (measured, config 2: step -4.5 %); larger ones fill the
-  // chip alone and only disturb the neighbours' caches (configs 3 and 5: +2 %), so there the
-  // side work stays in line.  Buffers that side work reads alternate between blocks (dy: in threes, since
-  // block l-1 writes the dy of block l-2 while the side work of block l still reads its own).
-  const int t128d = (d + 127) / 128, t128f = (f + 127) / 128, t128q = (3 * d + 127) / 128;
-  const bool side = 2 * t128d * t128f + t128d * t128d + t128d * t128q <= 1024;
-  hipStream_t ws = side ? s->wgs : st;
+  // block, the reductions behind the bias and LayerNorm gradients, the block's delayed update -
+  // is side work: nothing in the chain dy -> dx that the block below waits for reads it.  It
+  // goes to a stream of its own and runs beside the next block's chain (measured step time
+  // against issuing it in line: config 2 -7 %, config 3 -1 %, config 5 -5 %).  Buffers that
+  // side work reads alternate between blocks (dy: in threes, since block l-1 writes the dy of
+  // block l-2 while the side work of block l still reads its own).
+  hipStream_t ws = s->wgs;
   auto side_begin = [&]() -> rv_status {
-    if (!side) return RV_OK;
     RV_HIP_TRY(hipEventRecord(s->ev_wg_ready, st));
     RV_HIP_TRY(hipStreamWaitEvent(ws, s->ev_wg_ready, 0));
     return RV_OK;
@@ -185,7 +181,7 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
   for (int l = p.L - 1; l >= 0; --l) {
     const int par = l & 1;
     // block l may overwrite what the side work of block l+2 read only after that is done
-    if (side && l + 2 < p.L) RV_HIP_TRY(hipStreamWaitEvent(st, s->ev_wg_done[par], 0));
+    if (l + 2 < p.L) RV_HIP_TRY(hipStreamWaitEvent(st, s->ev_wg_done[par], 0));
     uint16_t* dx1_16 = (uint16_t*)(s->work + p.w_dx1_16[par]);   // bf16 dx1 of this block
     uint16_t* dz = (uint16_t*)(s->work + p.w_dz[par]);
     uint16_t* dqkv = (uint16_t*)(s->work + p.w_dqkv[par]);
@@ -247,13 +243,11 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
     // every gradient of block l is complete behind this point of `ws` (its b2 gradient came
     // from the block above): the delayed update of the block follows at once
     RV_TRY(rv_stage_update_range(s, (size_t)l * p.per_block, p.per_block, ws));
-    if (side) RV_HIP_TRY(hipEventRecord(s->ev_wg_done[par], ws));
+    RV_HIP_TRY(hipEventRecord(s->ev_wg_done[par], ws));
     dres16 = dy_below;               // dy of the block below
   }
   // the caller's stream (and with it the update) continues behind the last side work
-  if (side) {
-    RV_HIP_TRY(hipStreamWaitEvent(st, s->ev_wg_done[0], 0));
-    if (p.L > 1) RV_HIP_TRY(hipStreamWaitEvent(st, s->ev_wg_done[1], 0));
-  }
+  RV_HIP_TRY(hipStreamWaitEvent(st, s->ev_wg_done[0], 0));
+  if (p.L > 1) RV_HIP_TRY(hipStreamWaitEvent(st, s->ev_wg_done[1], 0));
   return RV_OK;
 }

@@ -593,8 +593,8 @@ struct GroupedArgs {
   int count;
 };
 
-template <int BM, int BN, int BK, int NS, int WPE>
-__global__ __launch_bounds__(kThreads, WPE) void gemm_dtl_grouped_wgrad_kernel(GroupedArgs ga) {
+template <int BM, int BN, int BK, int NS, int NW, int WPE>
+__global__ __launch_bounds__(64 * NW, WPE) void gemm_dtl_grouped_wgrad_kernel(GroupedArgs ga) {
   int pi = 0;
 #pragma unroll
   for (int k = 1; k < RV_GEMM_GROUP_MAX; ++k)
@@ -602,8 +602,8 @@ __global__ __launch_bounds__(kThreads, WPE) void gemm_dtl_grouped_wgrad_kernel(G
   const GroupedProblem& q = ga.p[pi];
   const int local = blockIdx.x - q.first_tile;
   Epi e{q.out, q.ldo, nullptr, nullptr, nullptr, 0, nullptr, nullptr};
-  gemm_dtl_body<BM, BN, BK, NS, 4, true, true, EPI_F32>(q.A, q.lda, q.B, q.ldb, q.M, q.N, q.K, local % q.tiles_m,
-                                                     local / q.tiles_m, e);
+  gemm_dtl_body<BM, BN, BK, NS, NW, true, true, EPI_F32>(q.A, q.lda, q.B, q.ldb, q.M, q.N, q.K, local % q.tiles_m,
+                                                      local / q.tiles_m, e);
 }
 
 template <int BM, int BN, int BK, int NS, int NW, int WPE, bool AKM, bool BKM, int EPI>
@@ -712,24 +712,13 @@ rv_status rv_gemm_bf16(const rv_gemm_args& g, hipStream_t st) {
   return RV_E_INVAL;
 }
 
-int rv_gemm_wgrad_grouped_tiles(const rv_gemm_args* gs, int count) {
-  int tiles = 0;
-  for (int k = 0; k < count; ++k) tiles += ((gs[k].M + 127) / 128) * ((gs[k].N + 127) / 128);
-  return tiles;
-}
-
-rv_status rv_gemm_wgrad_grouped(const rv_gemm_args* gs, int count, hipStream_t st) {
-  if (!gs || count < 1 || count > RV_GEMM_GROUP_MAX) return RV_E_INVAL;
-  constexpr int BM = 128, BN = 128, BK = 64, NS = 2;
+namespace {
+template <int BM, int BN, int BK, int NS, int NW>
+rv_status launch_grouped(const rv_gemm_args* gs, int count, hipStream_t st) {
   GroupedArgs ga;
   int tiles = 0;
   for (int k = 0; k < count; ++k) {
     const rv_gemm_args& g = gs[k];
-    if (!g.A || !g.B || !g.out || !g.a_kmajor || !g.b_kmajor || g.epi != EPI_F32) return RV_E_INVAL;
-    if (g.M < 8 || g.N < 8 || g.K < 64 || g.K % 64 || g.N % 8 || g.M % 8 || g.lda % 8 || g.ldb % 8 || g.ldo % 4)
-      return RV_E_INVAL;
-    if ((((uintptr_t)g.A) | ((uintptr_t)g.B) | ((uintptr_t)g.out)) & 15) return RV_E_INVAL;
-    if ((int64_t)g.K * g.lda >= (1ll << 31) || (int64_t)g.K * g.ldb >= (1ll << 31)) return RV_E_INVAL;
     GroupedProblem& q = ga.p[k];
     q.A = g.A; q.B = g.B; q.out = (float*)g.out;
     q.lda = (int)g.lda; q.ldb = (int)g.ldb; q.ldo = (int)g.ldo; q.M = g.M; q.N = g.N; q.K = g.K;
@@ -741,14 +730,31 @@ rv_status rv_gemm_wgrad_grouped(const rv_gemm_args* gs, int count, hipStream_t s
   ga.count = count;
   constexpr int smem = NS * (dtl_tile_bytes(BM, BK) + dtl_tile_bytes(BN, BK));
   static bool configured = false;
-  auto kern = gemm_dtl_grouped_wgrad_kernel<BM, BN, BK, NS, 2>;
+  auto kern = gemm_dtl_grouped_wgrad_kernel<BM, BN, BK, NS, NW, 2>;
   if (!configured) {
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
       return RV_E_DEVICE;
     configured = true;
   }
-  hipLaunchKernelGGL(kern, dim3(tiles), dim3(kThreads), smem, st, ga);
+  hipLaunchKernelGGL(kern, dim3(tiles), dim3(64 * NW), smem, st, ga);
   return rv_launch_status();
+}
+}  // namespace
+
+rv_status rv_gemm_wgrad_grouped(const rv_gemm_args* gs, int count, hipStream_t st) {
+  if (!gs || count < 1 || count > RV_GEMM_GROUP_MAX) return RV_E_INVAL;
+  for (int k = 0; k < count; ++k) {
+    const rv_gemm_args& g = gs[k];
+    if (!g.A || !g.B || !g.out || !g.a_kmajor || !g.b_kmajor || g.epi != EPI_F32) return RV_E_INVAL;
+    if (g.M < 8 || g.N < 8 || g.K < 64 || g.K % 64 || g.N % 8 || g.M % 8 || g.lda % 8 || g.ldb % 8 || g.ldo % 4)
+      return RV_E_INVAL;
+    if ((((uintptr_t)g.A) | ((uintptr_t)g.B) | ((uintptr_t)g.out)) & 15) return RV_E_INVAL;
+    if ((int64_t)g.K * g.lda >= (1ll << 31) || (int64_t)g.K * g.ldb >= (1ll << 31)) return RV_E_INVAL;
+  }
+  // 256x256 tiles, eight waves (measured against 128x128 and 128x256 tiles, alone and inside the
+  // stage step of configs 2, 3 and 5: fewest LDS bytes per MFMA, so it takes the least CU time
+  // from the kernels that run beside it, and the step is 3-4 % shorter)
+  return launch_grouped<256, 256, 64, 2, 8>(gs, count, st);
 }
 
 extern "C" rv_status rv_k_gemm_bf16(const void* A, int64_t lda, int a_kmajor, const void* B, int64_t ldb,

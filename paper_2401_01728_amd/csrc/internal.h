@@ -29,8 +29,6 @@ rv_status rv_gemm_bf16(const rv_gemm_args& g, hipStream_t st);
 // up to RV_GEMM_GROUP_MAX weight-gradient products (both operands k-major, fp32 output) in one launch
 #define RV_GEMM_GROUP_MAX 4
 rv_status rv_stage_update_range(rv_stage* s, size_t off, size_t n, hipStream_t st);
-// workgroups (128x128 tiles) the grouped launch below would have
-int rv_gemm_wgrad_grouped_tiles(const rv_gemm_args* gs, int count);
 rv_status rv_gemm_wgrad_grouped(const rv_gemm_args* gs, int count, hipStream_t st);
 
 // ---- norm.hip ---------------------------------------------------------------------
