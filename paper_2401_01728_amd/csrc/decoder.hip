@@ -92,10 +92,11 @@ void rv_dec_free(rv_stage* s) {
 
 namespace {
 
-rv_status gemm(hipStream_t st, const void* A, int64_t lda, int akm, const void* B, int64_t ldb, int bkm, int M,
+rv_status gemm(int sharing, hipStream_t st, const void* A, int64_t lda, int akm, const void* B, int64_t ldb, int bkm, int M,
                int N, int K, int epi, void* out, int64_t ldo, void* out2 = nullptr, const void* bias = nullptr,
                const float* resid = nullptr, const void* zin = nullptr) {
   rv_gemm_args g;
+  g.sharing = sharing;
   g.A = (const uint16_t*)A; g.lda = lda; g.a_kmajor = akm;
   g.B = (const uint16_t*)B; g.ldb = ldb; g.b_kmajor = bkm;
   g.M = M; g.N = N; g.K = K; g.epi = epi; g.out = out; g.ldo = ldo; g.out2 = out2;
@@ -110,6 +111,7 @@ rv_status rv_dec_forward(rv_stage* s, rv_slot& slot, const void* in, void* out) 
   const uint16_t* wv = (const uint16_t*)s->ver[slot.ver];
   hipStream_t st = s->st;
   const int T = p.T, d = p.d, f = p.f;
+  const int sh = s->in_step ? 2 : 0;   // in a step the backward chain is the longer one
   for (int l = 0; l < p.L; ++l) {
     const uint16_t* w = wv + (size_t)l * p.per_block;
     char* sb = slot.base + (size_t)l * p.blk_bytes;
@@ -127,17 +129,17 @@ rv_status rv_dec_forward(rv_stage* s, rv_slot& slot, const void* in, void* out) 
     else
       RV_TRY(rv_ln_fwd(x, 0, nullptr, w + p.ln1g, w + p.ln1b, u, (float*)(sb + p.s_m1), (float*)(sb + p.s_r1), T,
                        d, s->ln_eps, st));
-    RV_TRY(gemm(st, u, d, 0, w + p.wqkv, 3 * d, 1, T, 3 * d, d, RV_EPI_BF16_BIAS, qkv, 3 * d, nullptr, w + p.bqkv));
+    RV_TRY(gemm(sh, st, u, d, 0, w + p.wqkv, 3 * d, 1, T, 3 * d, d, RV_EPI_BF16_BIAS, qkv, 3 * d, nullptr, w + p.bqkv));
     RV_TRY(rv_attn_fwd(qkv, a, (float*)(sb + p.s_lse), p.mb, p.S, d, p.H, st));
-    RV_TRY(gemm(st, a, d, 0, w + p.wo, d, 1, T, d, d, RV_EPI_F32_BIAS_RESID, x1, d, nullptr, w + p.bo, x));
+    RV_TRY(gemm(sh, st, a, d, 0, w + p.wo, d, 1, T, d, d, RV_EPI_F32_BIAS_RESID, x1, d, nullptr, w + p.bo, x));
     RV_TRY(rv_ln_fwd(x1, 0, nullptr, w + p.ln2g, w + p.ln2b, v2, (float*)(sb + p.s_m2), (float*)(sb + p.s_r2), T, d,
                      s->ln_eps, st));
-    RV_TRY(gemm(st, v2, d, 0, w + p.w1, f, 1, T, f, d, RV_EPI_BF16_BIAS_GELU, z, f, g, w + p.b1));
+    RV_TRY(gemm(sh, st, v2, d, 0, w + p.w1, f, 1, T, f, d, RV_EPI_BF16_BIAS_GELU, z, f, g, w + p.b1));
     if (l + 1 < p.L) {
       float* xn = (float*)(slot.base + (size_t)(l + 1) * p.blk_bytes + p.s_x);
-      RV_TRY(gemm(st, g, f, 0, w + p.w2, d, 1, T, d, f, RV_EPI_F32_BIAS_RESID, xn, d, nullptr, w + p.b2, x1));
+      RV_TRY(gemm(sh, st, g, f, 0, w + p.w2, d, 1, T, d, f, RV_EPI_F32_BIAS_RESID, xn, d, nullptr, w + p.b2, x1));
     } else {
-      RV_TRY(gemm(st, g, f, 0, w + p.w2, d, 1, T, d, f, RV_EPI_F32_BIAS_RESID_BF16, s->work + p.w_ytmp, d, out,
+      RV_TRY(gemm(sh, st, g, f, 0, w + p.w2, d, 1, T, d, f, RV_EPI_F32_BIAS_RESID_BF16, s->work + p.w_ytmp, d, out,
                   w + p.b2, x1));
     }
   }
@@ -149,6 +151,7 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
   const uint16_t* wv = (const uint16_t*)s->ver[slot.ver];
   hipStream_t st = s->st;
   const int T = p.T, d = p.d, f = p.f;
+  const int sh = s->in_step ? 1 : 0;
   float* dres = (float*)(s->work + p.w_dres);
   uint16_t* dtmp = (uint16_t*)(s->work + p.w_dtmp);
   float* Dbuf = (float*)(s->work + p.w_D);
@@ -206,12 +209,12 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
     };
     // feed-forward half
     wgrad(0, g, f, dres16, d, f, d, gl + p.w2);                                                      // dW2 = g^T dy
-    RV_TRY(gemm(st, dres16, d, 0, w + p.w2, d, 0, T, f, d, RV_EPI_BF16_DGELU, dz, f, nullptr, nullptr, nullptr, z));
+    RV_TRY(gemm(sh, st, dres16, d, 0, w + p.w2, d, 0, T, f, d, RV_EPI_BF16_DGELU, dz, f, nullptr, nullptr, nullptr, z));
     wgrad(1, v2, d, dz, f, d, f, gl + p.w1);                                                         // dW1 = v2^T dz
     RV_TRY(side_begin());
     RV_TRY(rv_colsum_bf16(dz, f, T, f, part_cs, ws));
     RV_TRY(rv_reduce_rows(part_cs, cs_parts, f, f, gl + p.b1, ws));
-    RV_TRY(gemm(st, dz, f, 0, w + p.w1, f, 0, T, d, f, RV_EPI_BF16, dtmp, d));                       // dv2 = dz W1^T
+    RV_TRY(gemm(sh, st, dz, f, 0, w + p.w1, f, 0, T, d, f, RV_EPI_BF16, dtmp, d));                       // dv2 = dz W1^T
     RV_TRY(rv_ln_bwd(dtmp, x1, (const float*)(sb + p.s_m2), (const float*)(sb + p.s_r2), w + p.ln2g, dres, dres,
                      dx1_16, part2, T, d, st));
     {
@@ -222,14 +225,14 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
     }
     // attention half
     wgrad(2, a, d, dx1_16, d, d, d, gl + p.wo);                                                      // dWo = a^T dx1
-    RV_TRY(gemm(st, dx1_16, d, 0, w + p.wo, d, 0, T, d, d, RV_EPI_BF16, dtmp, d));                   // da = dx1 Wo^T
+    RV_TRY(gemm(sh, st, dx1_16, d, 0, w + p.wo, d, 0, T, d, d, RV_EPI_BF16, dtmp, d));                   // da = dx1 Wo^T
     RV_TRY(rv_attn_bwd(qkv, a, dtmp, (const float*)(sb + p.s_lse), Dbuf, dqkv, p.mb, p.S, d, p.H, st));
     wgrad(3, u, d, dqkv, 3 * d, d, 3 * d, gl + p.wqkv);                                              // dWqkv = u^T dqkv
     RV_TRY(side_begin());
     RV_TRY(rv_gemm_wgrad_grouped(wg, 4, ws));
     RV_TRY(rv_colsum_bf16(dqkv, 3 * d, T, 3 * d, part_cs, ws));
     RV_TRY(rv_reduce_rows(part_cs, cs_parts, 3 * d, 3 * d, gl + p.bqkv, ws));
-    RV_TRY(gemm(st, dqkv, 3 * d, 0, w + p.wqkv, 3 * d, 0, T, d, 3 * d, RV_EPI_BF16, dtmp, d));       // du
+    RV_TRY(gemm(sh, st, dqkv, 3 * d, 0, w + p.wqkv, 3 * d, 0, T, d, 3 * d, RV_EPI_BF16, dtmp, d));       // du
     uint16_t* dx16 = l == 0 ? (uint16_t*)grad_in : dy_below;
     RV_TRY(rv_ln_bwd(dtmp, x, (const float*)(sb + p.s_m1), (const float*)(sb + p.s_r1), w + p.ln1g, dres, dres, dx16,
                      part1, T, d, st));

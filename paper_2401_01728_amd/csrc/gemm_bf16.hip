@@ -662,6 +662,12 @@ rv_status pick_tile(const rv_gemm_args& g, hipStream_t st) {
     return (double)rounds * bm * bn * bpc / eff;
   };
   int tile = g.tile;
+  if (tile == 0 && g.sharing) {
+    // Measured inside the stage step (configs 2, 3, 5): what a launch leaves of the chip is
+    // used by the other streams, so CU time per flop counts for more than its own duration.
+    const long t256 = (long)((g.M + 255) / 256) * ((g.N + 255) / 256);
+    if (g.sharing == 2 || t256 >= 128) tile = 5256;
+  }
   if (tile == 0) {
     const double c256 = cost(256, 256, 1, 1.0), c192 = cost(128, 256, 2, 0.92), c128 = cost(128, 128, 2, 0.85);
     tile = c256 <= c192 && c256 <= c128 ? 5256 : (c192 <= c128 ? 2192 : 2128);

@@ -24,6 +24,12 @@ struct rv_gemm_args {
   const float* resid = nullptr; int64_t ldr = 0;
   const uint16_t* zin = nullptr;          // bf16 [M, ldo] pre-activations for GELU'
   int tile = 0;                           // 0 = choose, 128 or 256 = force
+  // who else is on the chip while this product runs (automatic tile choice only):
+  //   0  nobody: shortest time of this launch alone
+  //   1  the other streams of a stage step, and the launch is on the step's critical chain:
+  //      the 256x256 tile as soon as it covers half the chip
+  //   2  the same, off the critical chain: always the 256x256 tile (least CU time per flop)
+  int sharing = 0;
 };
 rv_status rv_gemm_bf16(const rv_gemm_args& g, hipStream_t st);
 // up to RV_GEMM_GROUP_MAX weight-gradient products (both operands k-major, fp32 output) in one launch
@@ -69,6 +75,7 @@ struct rv_stage {
   // third stream: the weight-gradient products of a decoder block run beside the next block's
   // input-gradient chain
   int upd_dst = -1;           // version slot the running backward publishes into
+  bool in_step = false;       // inside rv_stage_step: forward and backward share the chip
   hipStream_t wgs = nullptr;
   hipEvent_t ev_wg_ready = nullptr, ev_wg_done[2] = {nullptr, nullptr};
   size_t P = 0;

@@ -229,12 +229,14 @@ extern "C" rv_status rv_stage_step(rv_stage* s, int64_t fwd_mb, const void* in, 
   hipStream_t main_st = s->st;
   RV_HIP_TRY(hipEventRecord(s->ev_fork, main_st));
   RV_HIP_TRY(hipStreamWaitEvent(s->aux, s->ev_fork, 0));
+  s->in_step = true;
   rv_status rc = do_forward(s, fwd_mb, in, out);
   if (rc == RV_OK) {
     s->st = s->aux;
     rc = do_backward(s, bi, grad_out, grad_in, true);
     s->st = main_st;
   }
+  s->in_step = false;
   // join even after a failure so the caller's stream stays ordered behind the aux work
   hipError_t e1 = hipEventRecord(s->ev_join, s->aux);
   hipError_t e2 = hipStreamWaitEvent(main_st, s->ev_join, 0);
