@@ -8,6 +8,8 @@ Workloads (synthetic, seeded; see the design doc for the recipes):
           16 heads, FFN 4096, seq 512, microbatch 8, tau 2.  A step is the steady-state
           stage step: forward(t), backward(t - tau), delayed SGD update.  tokens/s.
   stage3 / stage5   the larger decoder stages, same step.
+  gemm    one bf16 matrix product alone (--shape M,N,K, --layout fwd|dgrad|wgrad, --operands
+          normal|zeros|ones): the kernel under the stage step, for counter runs.  TFLOP/s.
   avg4    the averaging-dominated case: 1e9 fp32 elements, C = 16 replicas in HBM, ring
           partitioned mean with one replica's SGD step folded in; a step is one call.
 The oracle (CPU fp64) is timed beside it on a bounded sample ("cpu_baseline").
@@ -122,6 +124,29 @@ def cpu_average(C, R, eta, seed):
             "sample": "oracle.average.direct_mean (fp64) on N=%d, C=%d, %d calls" % (n, C, reps)}
 
 
+def bench_gemm(args):
+    """One matrix product through its per-kernel entry point (automatic tile choice)."""
+    import torch
+    from paper_2401_01728_amd import kernels as kk
+    M, N, K = [int(v) for v in args.shape.split(",")]
+    akm, bkm, epi = {"fwd": (0, 1, kk.EPI_BF16_BIAS), "dgrad": (0, 0, kk.EPI_BF16), "wgrad": (1, 1, kk.EPI_F32)}[args.layout]
+
+    def operand(r, c, std):
+        t = torch.empty(r, c, dtype=torch.bfloat16, device="cuda")
+        return {"normal": lambda: t.normal_(std=std), "zeros": t.zero_, "ones": lambda: t.fill_(1.0)}[args.operands]()
+    A = operand(K, M, 1.0) if akm else operand(M, K, 1.0)
+    B = operand(K, N, 0.02) if bkm else operand(N, K, 0.02)
+    out = torch.empty(M, N, dtype=torch.float32 if epi == kk.EPI_F32 else torch.bfloat16, device="cuda")
+    bias = torch.zeros(N, dtype=torch.bfloat16, device="cuda")
+    ms, _ = events_ms(lambda: kk.gemm_bf16(A, akm, B, bkm, M, N, K, epi, out, bias=bias), args.steps, args.warmup)
+    tf = 2.0 * M * N * K / (ms * 1e-3) / 1e12
+    return {"metric": "bf16 matrix product TFLOP/s", "value": tf, "unit": "TFLOP/s", "ms_per_step": ms, "dtype": "bf16",
+            "config": {"workload": "gemm: M=%d N=%d K=%d %s, operands %s" % (M, N, K, args.layout, args.operands)},
+            "roofline": {"bound": "mfma", "achieved": tf, "peak": BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": tf / BF16_PEAK_TFLOPS, "traffic": None, "kernel": "gemm_dtl_kernel",
+                         "algorithmic_flops_per_launch": 2.0 * M * N * K}}
+
+
 def bench_stage(args, name):
     import torch
     import paper_2401_01728_amd as rv
@@ -231,6 +256,9 @@ def main():
     ap.add_argument("--workload", default=None)
     ap.add_argument("--rings", type=int, default=4)
     ap.add_argument("--n", type=float, default=None)
+    ap.add_argument("--shape", default="8192,8192,8192", help="gemm: M,N,K")
+    ap.add_argument("--layout", default="dgrad", choices=["fwd", "dgrad", "wgrad"])
+    ap.add_argument("--operands", default="normal", choices=["normal", "zeros", "ones"])
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--calib-copy", action="store_true", help="avg4: also run one plain 4*n-byte copy (counter calibration)")
     ap.add_argument("--no-overlap", action="store_true",
@@ -245,7 +273,7 @@ def main():
     from paper_2401_01728_amd import _lib
     _lib.lib()                                              # fail loudly if the HIP library is missing
     wl = args.workload or "stage2"
-    res = bench_avg4(args) if wl == "avg4" else bench_stage(args, wl)
+    res = bench_avg4(args) if wl == "avg4" else bench_gemm(args) if wl == "gemm" else bench_stage(args, wl)
     res.update({"n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True,
                 "scaling": "weak", "vs_baseline": None, "data": "synthetic"})
     print(json.dumps(res))
