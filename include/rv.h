@@ -114,6 +114,17 @@ rv_status rv_stage_last_grad(const rv_stage* s, float* flat_out, size_t n);
 rv_status rv_stage_set_optimizer(rv_stage* s, float momentum, float weight_decay);
 
 /*
+ * Optional: gradient accumulation as in the paper's multi-cluster experiment (section 4.2): the
+ * gradients of `microbatches` consecutive backward calls are summed and the update (Eq. 2, or
+ * the optimiser set above) is applied once, with the sum, by the last of them; the others
+ * leave the parameters and the current weight version as they are.  1 = update on every
+ * backward (the default).  Only legal with no microbatch in flight; a group in progress is
+ * dropped.  Allocates an fp32 [P] accumulator on first use.  rv_stage_last_grad keeps
+ * returning the last microbatch's own gradient.
+ */
+rv_status rv_stage_set_accumulation(rv_stage* s, int microbatches);
+
+/*
  * Forward branch of Alg. 1: out = forward_pass(x_{c,p}, in) at the CURRENT
  * parameters.  Binds mb_id to a stash slot and to the current weight version.
  * in/out: device, MLP fp32 [microbatch, dims[0]] -> [microbatch, dims[n_layers]];

@@ -31,7 +31,7 @@ class DuplicateMicrobatch(Exception):
 
 class Stage:
     def __init__(self, kind, tau, eta, flat_w, *, dims=None, n_blocks=None, d=None, h=None,
-                 f=None, eps=1e-5, momentum=0.0, weight_decay=0.0):
+                 f=None, eps=1e-5, momentum=0.0, weight_decay=0.0, accumulate=1):
         assert kind in ("mlp", "decoder")
         self.kind, self.tau, self.eta = kind, int(tau), float(eta)
         self.dims, self.n_blocks, self.d, self.h, self.f, self.eps = dims, n_blocks, d, h, f, eps
@@ -44,6 +44,11 @@ class Stage:
         # momentum and weight decay; both zero = the plain step of Eq. 2
         self.momentum, self.weight_decay = float(momentum), float(weight_decay)
         self.v = np.zeros_like(self.w)
+        # gradient accumulation of the paper's multi-cluster experiment (section 4.2: gradients
+        # of several microbatches are summed before one update); 1 = update on every backward
+        self.accumulate = int(accumulate)
+        self.g_sum = np.zeros_like(self.w)
+        self.n_sum = 0
 
     def _f(self, w, x):
         if self.kind == "mlp":
@@ -70,13 +75,20 @@ class Stage:
             raise UnknownMicrobatch(mb_id)
         w_mb, x, k_fwd = self.live.pop(mb_id)
         dx, g = self._vjp(w_mb, x, np.array(dy, dtype=np.float64))
+        self.last_grad = g
+        self.last_staleness = self.k - k_fwd
+        self.g_sum = self.g_sum + g
+        self.n_sum += 1
+        if self.n_sum < self.accumulate:
+            return dx                                           # no update yet: k counts updates
+        g = self.g_sum
+        self.g_sum = np.zeros_like(self.w)
+        self.n_sum = 0
         if self.momentum == 0.0 and self.weight_decay == 0.0:
             self.w = self.w - self.eta * g                      # Eq. 2
         else:
             d = g + self.weight_decay * self.w
             self.v = self.momentum * self.v + d
             self.w = self.w - self.eta * self.v
-        self.last_grad = g
-        self.last_staleness = self.k - k_fwd
         self.k += 1
         return dx

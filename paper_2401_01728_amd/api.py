@@ -95,6 +95,9 @@ class Stage:
     def set_optimizer(self, momentum=0.0, weight_decay=0.0):
         _check(_lib.lib().rv_stage_set_optimizer(self._h, momentum, weight_decay))
 
+    def set_accumulation(self, microbatches):
+        _check(_lib.lib().rv_stage_set_accumulation(self._h, int(microbatches)))
+
     def get_params(self, out=None):
         if out is None:
             out = torch.empty(self.num_params, dtype=torch.float32, device="cuda")

@@ -9,6 +9,7 @@ rv_status rv_launch_update(float* w, const float* g, size_t n, float eta, void* 
                            hipStream_t st);
 rv_status rv_launch_update_momentum(float* w, const float* g, float* v, size_t n, float eta, float mu, float wd,
                                     void* copy, int copy_kind, hipStream_t st);
+rv_status rv_launch_accumulate(float* acc, const float* g, size_t n, bool first, hipStream_t st);
 rv_status rv_launch_publish(const float* w, size_t n, void* copy, int copy_kind, hipStream_t st);
 
 // ---- gemm_bf16.hip ----------------------------------------------------------------
@@ -83,6 +84,8 @@ struct rv_stage {
   float* grad = nullptr;    // [P] fp32, gradient of the last backward
   float* vel = nullptr;     // [P] fp32 momentum buffer (allocated by rv_stage_set_optimizer)
   float momentum = 0.f, weight_decay = 0.f;
+  float* gacc = nullptr;    // [P] fp32 sum of the gradients of the current accumulation group
+  int accum = 1, acc_count = 0;   // microbatches per update; backwards so far in the group
   size_t ver_elem = 0;      // bytes per parameter in a version slot (2 or 4)
   std::vector<char*> ver;   // tau+1 version slots
   std::vector<int> ver_ref; // in-flight microbatches bound to each slot

@@ -31,6 +31,7 @@ void free_all(rv_stage* s) {
   if (s->master) (void)hipFree(s->master);
   if (s->grad) (void)hipFree(s->grad);
   if (s->vel) (void)hipFree(s->vel);
+  if (s->gacc) (void)hipFree(s->gacc);
   for (char* v : s->ver) if (v) (void)hipFree(v);
   if (s->stash) (void)hipFree(s->stash);
   if (s->work) (void)hipFree(s->work);
@@ -126,6 +127,17 @@ extern "C" rv_status rv_stage_set_optimizer(rv_stage* s, float momentum, float w
   return RV_OK;
 }
 
+extern "C" rv_status rv_stage_set_accumulation(rv_stage* s, int microbatches) {
+  if (!s || microbatches < 1) return RV_E_INVAL;
+  if (rv_stage_in_flight(s) != 0) return RV_E_INVAL;
+  if (microbatches > 1 && !s->gacc) {
+    if (hipMalloc((void**)&s->gacc, s->P * 4) != hipSuccess) { (void)hipGetLastError(); s->gacc = nullptr; return RV_E_NOMEM; }
+  }
+  s->accum = microbatches;
+  s->acc_count = 0;     // a group in progress is dropped
+  return RV_OK;
+}
+
 extern "C" rv_status rv_stage_get_params(const rv_stage* s, float* flat_out, size_t n) {
   if (!s || !flat_out || n != s->P) return RV_E_INVAL;
   RV_HIP_TRY(hipMemcpyAsync(flat_out, s->master, n * 4, hipMemcpyDeviceToDevice, s->st));
@@ -142,11 +154,17 @@ extern "C" rv_status rv_stage_last_grad(const rv_stage* s, float* flat_out, size
 // into the version slot chosen for this backward
 rv_status rv_stage_update_range(rv_stage* s, size_t off, size_t n, hipStream_t st) {
   const int kind = s->dtype == RV_BF16 ? 1 : 2;
+  const float* g = s->grad + off;
+  if (s->accum > 1) {   // sum the group's gradients; only its last microbatch updates
+    RV_TRY(rv_launch_accumulate(s->gacc + off, g, n, s->acc_count == 0, st));
+    if (s->acc_count + 1 < s->accum) return RV_OK;
+    g = s->gacc + off;
+  }
   void* copy = (char*)s->ver[s->upd_dst] + off * s->ver_elem;
   if (s->vel)
-    return rv_launch_update_momentum(s->master + off, s->grad + off, s->vel + off, n, s->eta, s->momentum,
-                                     s->weight_decay, copy, kind, st);
-  return rv_launch_update(s->master + off, s->grad + off, n, s->eta, copy, kind, st);
+    return rv_launch_update_momentum(s->master + off, g, s->vel + off, n, s->eta, s->momentum, s->weight_decay,
+                                     copy, kind, st);
+  return rv_launch_update(s->master + off, g, n, s->eta, copy, kind, st);
 }
 
 namespace {
@@ -176,12 +194,17 @@ rv_status do_backward(rv_stage* s, int slot_i, const void* grad_out, void* grad_
   // slot is chosen before the backward so that a stage kind may update layer by layer as the
   // gradients complete; a layer's weights are not read again once its gradient exists, so
   // this is safe even when the slot is the one this backward reads.
+  // With gradient accumulation only the last microbatch of a group updates; the others leave
+  // the current version in force.
+  const bool updates = s->acc_count + 1 >= s->accum;
   int dst = -1;
   auto refs = [&](size_t v) { return s->ver_ref[v] - ((int)v == sl.ver ? 1 : 0); };
-  if (!never_in_place && refs(s->cur) == 0) dst = s->cur;
-  for (size_t v = 0; dst < 0 && v < s->ver.size(); ++v)
-    if (refs(v) == 0 && !(never_in_place && (int)v == s->cur)) dst = (int)v;
-  if (dst < 0) return RV_E_DEVICE;  // unreachable by the counting argument above
+  if (updates) {
+    if (!never_in_place && refs(s->cur) == 0) dst = s->cur;
+    for (size_t v = 0; dst < 0 && v < s->ver.size(); ++v)
+      if (refs(v) == 0 && !(never_in_place && (int)v == s->cur)) dst = (int)v;
+    if (dst < 0) return RV_E_DEVICE;  // unreachable by the counting argument above
+  }
   s->upd_dst = dst;
   rv_status rc;
   if (s->kind == RV_MLP) {
@@ -194,7 +217,8 @@ rv_status do_backward(rv_stage* s, int slot_i, const void* grad_out, void* grad_
   sl.live = false;
   s->ver_ref[sl.ver] -= 1;
   sl.ver = -1;
-  s->cur = dst;
+  if (updates) { s->cur = dst; s->acc_count = 0; }
+  else s->acc_count += 1;
   return RV_OK;
 }
 

@@ -117,6 +117,30 @@ __global__ __launch_bounds__(kThreads) void update_momentum_kernel(float* __rest
   }
 }
 
+// Gradient accumulation (section 4.2 of the paper: the gradients of several microbatches are
+// summed before one update): acc <- g for the first microbatch of a group, acc <- acc + g
+// after.  12 B/param (8 for the first).
+template <bool FIRST>
+__global__ __launch_bounds__(kThreads) void accumulate_kernel(float* __restrict__ acc, const float* __restrict__ g,
+                                                              uint64_t n, int aligned) {
+  const uint64_t base = (uint64_t)blockIdx.x * kTile;
+  if (aligned && base + kTile <= n) {
+#pragma unroll
+    for (int u = 0; u < kVec; ++u) {
+      const uint64_t e = base + (uint64_t)(u * kThreads + threadIdx.x) * 4;
+      f4 gv = *reinterpret_cast<const f4*>(g + e);
+      if (!FIRST) gv += *reinterpret_cast<const f4*>(acc + e);
+      *reinterpret_cast<f4*>(acc + e) = gv;
+    }
+    return;
+  }
+  for (int k = threadIdx.x; k < kTile; k += kThreads) {
+    const uint64_t i = base + k;
+    if (i >= n) break;
+    acc[i] = FIRST ? g[i] : acc[i] + g[i];
+  }
+}
+
 // plain conversion of the master vector into a version slot (set_params)
 template <int COPY>
 __global__ __launch_bounds__(kThreads) void publish_kernel(const float* __restrict__ w, uint64_t n,
@@ -156,6 +180,15 @@ rv_status rv_launch_update_momentum(float* w, const float* g, float* v, size_t n
     hipLaunchKernelGGL(update_momentum_kernel<1>, dim3(blocks), dim3(kThreads), 0, st, w, g, v, n, eta, mu, wd, copy, aligned);
   else
     hipLaunchKernelGGL(update_momentum_kernel<2>, dim3(blocks), dim3(kThreads), 0, st, w, g, v, n, eta, mu, wd, copy, aligned);
+  return rv_launch_status();
+}
+
+rv_status rv_launch_accumulate(float* acc, const float* g, size_t n, bool first, hipStream_t st) {
+  if (n == 0) return RV_OK;
+  const int aligned = ((((uintptr_t)acc) | ((uintptr_t)g)) & 15) == 0;
+  const unsigned blocks = (unsigned)((n + kTile - 1) / kTile);
+  if (first) hipLaunchKernelGGL(accumulate_kernel<true>, dim3(blocks), dim3(kThreads), 0, st, acc, g, n, aligned);
+  else hipLaunchKernelGGL(accumulate_kernel<false>, dim3(blocks), dim3(kThreads), 0, st, acc, g, n, aligned);
   return rv_launch_status();
 }
 

@@ -148,3 +148,34 @@ def test_decoder_error_paths():
     assert e.value.status == rv.api.RV_E_UNKNOWN_MB
     g.backward(1, x); g.backward(0, x)
     assert g.in_flight == 0
+
+
+def test_decoder_stage_with_accumulation_in_fused_steps():
+    """Gradient accumulation (section 4.2) through rv_stage_step: block-wise accumulate / update on
+    the side stream, forwards bound to a version that only every second backward replaces."""
+    import paper_2401_01728_amd as rv
+    L, d, H, f, S, mb, tau, A, eta = 2, 128, 2, 256, 128, 2, 2, 2, 1e-2
+    shapes = blocks.decoder_param_shapes(L, d, f)
+    w0 = decoder_params_host(31, L, d, f)
+    g = rv.Stage.decoder(L, d, H, f, S, mb, tau, eta); g.set_params(dev(w0)); g.set_accumulation(A)
+    o = ostage.Stage("decoder", tau, eta, w0, n_blocks=L, d=d, h=H, f=f, accumulate=A)
+    n = 7
+    for t in range(n + tau):
+        j = t - tau
+        if t < n:
+            x, x64 = bf16_normal(31, 1000 + t, (mb, S, d))
+        if j >= 0:
+            dy, dy64 = bf16_normal(31, 2000 + j, (mb, S, d), std=1e-3)
+        if t < n and j >= 0:
+            y, dx = g.step(t, x, j, dy)
+        elif t < n:
+            y = g.forward(t, x)
+        else:
+            dx = g.backward(j, dy)
+        if t < n:
+            assert rel_l2(host64(y), o.forward(t, x64)) < TOL
+        if j >= 0:
+            assert rel_l2(host64(dx), o.backward(j, dy64)) < TOL
+            check_tensors(host64(g.last_grad()), o.last_grad, shapes, what="grad step %d" % j)
+    assert o.k == n // A
+    assert rel_l2(host64(g.get_params()) - w0, o.w - w0) < TOL

@@ -153,3 +153,32 @@ def test_stage_with_momentum_and_weight_decay():
     assert rel_l2(host64(g.get_params()) - w0, o.w - w0) < 1e-4
     with pytest.raises(rv.RvError):
         g.set_optimizer(-1.0, 0.0)
+
+
+@pytest.mark.parametrize("A,momentum", [(3, 0.0), (2, 0.9)])
+def test_stage_with_gradient_accumulation(A, momentum):
+    """Section 4.2: the gradients of A microbatches are summed before one update; the parameters
+    stay put in between and the staleness is counted in updates."""
+    import paper_2401_01728_amd as rv
+    dims, mb, tau, eta = [33, 17, 9], 6, 1, 0.05
+    w0 = kaiming_uniform_flat(8, dims)
+    g = rv.Stage.mlp(dims, mb, tau, eta); g.set_params(dev(w0)); g.set_accumulation(A)
+    o = ostage.Stage("mlp", tau, eta, w0, dims=dims, accumulate=A, momentum=momentum)
+    if momentum:
+        g.set_optimizer(momentum, 0.0)
+    n = 3 * A + 1                                            # ends inside a group
+    for t in range(n + tau):
+        if t < n:
+            x = gen.normal_f32(8, 10 + t, mb * dims[0]).reshape(mb, dims[0])
+            assert rel_l2(host64(g.forward(t, dev(x))), o.forward(t, x)) < 1e-5
+        j = t - tau
+        if j >= 0:
+            dy = gen.normal_f32(8, 50 + j, mb * dims[-1]).reshape(mb, dims[-1])
+            before = g.get_params().clone()
+            assert rel_l2(host64(g.backward(j, dev(dy))), o.backward(j, dy)) < 1e-5
+            assert rel_l2(host64(g.last_grad()), o.last_grad) < 1e-5
+            moved = not torch.equal(before, g.get_params())
+            assert moved == ((j + 1) % A == 0)
+    assert rel_l2(host64(g.get_params()) - w0, o.w - w0) < 1e-4
+    with pytest.raises(rv.RvError):
+        g.set_accumulation(0)

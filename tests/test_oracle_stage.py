@@ -155,3 +155,48 @@ def test_momentum_against_separate_loop():
         _, g = blocks.mlp_backward(w, dims, x, dy)
         v = mu * v + (g + wd * w); w = w - eta * v
     assert np.allclose(st.w, w, rtol=0, atol=1e-15)
+
+
+def test_accumulation_equals_one_backward_on_the_stacked_batch():
+    """Section 4.2: gradients of A microbatches are summed before one update.  With no update in
+    between, A microbatches see the same weights, so the sum of their gradients is the gradient
+    of the stacked batch (the layers act row by row) - computed here by a stage that never
+    accumulates."""
+    rng = np.random.default_rng(5)
+    dims, eta = [4, 6, 3], 0.05
+    w0 = rng.normal(size=51) * 0.5
+    xs = [rng.normal(size=(5, 4)) for _ in range(3)]
+    dys = [rng.normal(size=(5, 3)) for _ in range(3)]
+    a = stage.Stage("mlp", 0, eta, w0, dims=dims, accumulate=3)
+    for t in range(3):
+        a.forward(t, xs[t])
+        assert np.array_equal(a.w, w0)                      # nothing moves before the third backward
+        a.backward(t, dys[t])
+    b = stage.Stage("mlp", 0, eta, w0, dims=dims)
+    b.forward(0, np.concatenate(xs)); b.backward(0, np.concatenate(dys))
+    assert np.allclose(a.w, b.w, rtol=0, atol=1e-14)
+    assert a.k == 1 and a.n_sum == 0
+
+
+def test_accumulation_with_staleness_against_separate_loop():
+    rng = np.random.default_rng(6)
+    dims, eta, tau, A, n = [4, 6, 3], 0.05, 1, 2, 8
+    w0 = rng.normal(size=51) * 0.5
+    st = stage.Stage("mlp", tau, eta, w0, dims=dims, accumulate=A)
+    xs = [rng.normal(size=(5, 4)) for _ in range(n)]
+    dys = [rng.normal(size=(5, 3)) for _ in range(n)]
+    w = w0.copy(); seen = {}; acc = np.zeros_like(w); cnt = 0; stal = []
+    updates = 0; fwd_k = {}
+    for t in range(n + tau):
+        if t < n:
+            st.forward(t, xs[t]); seen[t] = w.copy(); fwd_k[t] = updates
+        j = t - tau
+        if j >= 0:
+            st.backward(j, dys[j]); stal.append(st.last_staleness)
+            _, g = blocks.mlp_backward(seen.pop(j), dims, xs[j], dys[j])
+            assert stal[-1] == updates - fwd_k[j]
+            acc += g; cnt += 1
+            if cnt == A:
+                w = w - eta * acc; acc = np.zeros_like(w); cnt = 0; updates += 1
+    assert np.allclose(st.w, w, rtol=0, atol=1e-15)
+    assert max(stal) == 1 and min(stal) == 0               # staleness is counted in updates
