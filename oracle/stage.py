@@ -70,13 +70,17 @@ class Stage:
         self.live[mb_id] = (w_mb, x, self.k)
         return self._f(w_mb, x)
 
-    def backward(self, mb_id, dy):
+    def backward(self, mb_id, dy, defer=False):
+        """defer: compute the gradient but leave the update pending (Alg. 2: at an averaging
+        step the sampled peer's update is folded into the all-reduce instead)."""
         if mb_id not in self.live:
             raise UnknownMicrobatch(mb_id)
         w_mb, x, k_fwd = self.live.pop(mb_id)
         dx, g = self._vjp(w_mb, x, np.array(dy, dtype=np.float64))
         self.last_grad = g
         self.last_staleness = self.k - k_fwd
+        if defer:
+            return dx
         self.g_sum = self.g_sum + g
         self.n_sum += 1
         if self.n_sum < self.accumulate:
@@ -92,3 +96,8 @@ class Stage:
             self.w = self.w - self.eta * self.v
         self.k += 1
         return dx
+
+    def install(self, w):
+        """Parameters replaced from outside (the cluster average): a new weight version."""
+        self.w = np.array(w, dtype=np.float64)
+        self.k += 1
