@@ -166,6 +166,24 @@ rv_status rv_stage_step(rv_stage* s, int64_t fwd_mb, const void* in, void* out, 
 rv_status rv_block_update(float* w, const float* g, size_t n, float eta, void* bf16_out,
                           void* stream);
 
+/*
+ * The all-reduce branch of the method's outer loop (Alg. 2): C clusters hold one stage each for
+ * the same block of layers (same parameter count and dtype, created on the same stream, all
+ * resident in this GPU's HBM).  rv_cluster_sync replaces every stage's parameters by their
+ * ring-partitioned mean over R rings (rv_cluster_average with write-back on the fp32 master
+ * vectors) and makes the mean each stage's current weight version; microbatches in flight keep
+ * the versions they were forwarded with.  pending = index of the stage whose last backward ran
+ * with its update deferred: its step x - eta * g is folded into the mean (Eq. 17); -1 = none.
+ * RV_E_STASH_FULL if a stage has no version slot free of in-flight microbatches.
+ *
+ * rv_stage_defer_update(s, 1): following backward / step calls compute grad_in and the
+ * parameter gradient but leave parameters and weight version untouched (Alg. 2 folds the
+ * sampled peer's step into the all-reduce at an averaging step); 0 restores Eq. 2 on every
+ * backward.  Not combinable with gradient accumulation or the momentum optimiser.
+ */
+rv_status rv_stage_defer_update(rv_stage* s, int on);
+rv_status rv_cluster_sync(rv_stage* const* stages, int C, int R, int pending);
+
 /* The momentum / weight-decay step above on bare vectors; v (device [n]) is read and updated. */
 rv_status rv_block_update_momentum(float* w, const float* g, float* v, size_t n, float eta, float momentum,
                                    float weight_decay, void* bf16_out, void* stream);

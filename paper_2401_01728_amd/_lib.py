@@ -26,6 +26,8 @@ SYMBOLS = {
     "rv_stage_set_params": (c_int, [c_void_p, c_void_p, c_size_t]),
     "rv_stage_set_optimizer": (c_int, [c_void_p, c_float, c_float]),
     "rv_stage_set_accumulation": (c_int, [c_void_p, c_int]),
+    "rv_stage_defer_update": (c_int, [c_void_p, c_int]),
+    "rv_cluster_sync": (c_int, [c_void_p, c_int, c_int, c_int]),
     "rv_stage_get_params": (c_int, [c_void_p, c_void_p, c_size_t]),
     "rv_stage_last_grad": (c_int, [c_void_p, c_void_p, c_size_t]),
     "rv_stage_forward": (c_int, [c_void_p, c_int64, c_void_p, c_void_p]),

@@ -98,6 +98,9 @@ class Stage:
     def set_accumulation(self, microbatches):
         _check(_lib.lib().rv_stage_set_accumulation(self._h, int(microbatches)))
 
+    def defer_update(self, on=True):
+        _check(_lib.lib().rv_stage_defer_update(self._h, 1 if on else 0))
+
     def get_params(self, out=None):
         if out is None:
             out = torch.empty(self.num_params, dtype=torch.float32, device="cuda")
@@ -161,6 +164,13 @@ def block_update_momentum(w, g, v, eta, momentum, weight_decay, bf16_out=None, s
     _dev_f32(w); _dev_f32(g, w.numel()); _dev_f32(v, w.numel())
     _check(_lib.lib().rv_block_update_momentum(_ptr(w), _ptr(g), _ptr(v), w.numel(), eta, momentum, weight_decay,
                                                _ptr(bf16_out), _stream_handle(stream)))
+
+
+def cluster_sync(stages, R, pending=-1):
+    """rv_cluster_sync: every stage's parameters become their ring-partitioned mean (Alg. 2)."""
+    import ctypes
+    arr = (ctypes.c_void_p * len(stages))(*[s._h for s in stages])
+    _check(_lib.lib().rv_cluster_sync(arr, len(stages), R, pending))
 
 
 def cluster_average(replicas, R, mean_out=None, write_back=False, grad=None, grad_replica=0, eta=0.0,

@@ -86,6 +86,7 @@ struct rv_stage {
   float momentum = 0.f, weight_decay = 0.f;
   float* gacc = nullptr;    // [P] fp32 sum of the gradients of the current accumulation group
   int accum = 1, acc_count = 0;   // microbatches per update; backwards so far in the group
+  bool defer = false;       // backward leaves its update pending (folded into the next cluster sync)
   size_t ver_elem = 0;      // bytes per parameter in a version slot (2 or 4)
   std::vector<char*> ver;   // tau+1 version slots
   std::vector<int> ver_ref; // in-flight microbatches bound to each slot

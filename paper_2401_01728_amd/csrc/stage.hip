@@ -138,6 +138,43 @@ extern "C" rv_status rv_stage_set_accumulation(rv_stage* s, int microbatches) {
   return RV_OK;
 }
 
+extern "C" rv_status rv_stage_defer_update(rv_stage* s, int on) {
+  if (!s) return RV_E_INVAL;
+  if (on && (s->accum > 1 || s->vel)) return RV_E_INVAL;   // the folded step is the plain one of Alg. 2
+  s->defer = on != 0;
+  return RV_OK;
+}
+
+extern "C" rv_status rv_cluster_sync(rv_stage* const* stages, int C, int R, int pending) {
+  if (!stages || C < 1 || C > 64 || R < 1 || pending < -1 || pending >= C) return RV_E_INVAL;
+  float* masters[64];
+  for (int c = 0; c < C; ++c) {
+    rv_stage* s = stages[c];
+    if (!s || s->P != stages[0]->P || s->dtype != stages[0]->dtype || s->st != stages[0]->st) return RV_E_INVAL;
+    for (int k = 0; k < c; ++k) if (stages[k] == s) return RV_E_INVAL;
+    if (s->accum > 1 && s->acc_count != 0) return RV_E_INVAL;   // a gradient group is open
+    masters[c] = s->master;
+  }
+  // every stage needs a version slot that no in-flight microbatch is bound to
+  int dst[64];
+  for (int c = 0; c < C; ++c) {
+    rv_stage* s = stages[c];
+    dst[c] = s->ver_ref[s->cur] == 0 ? s->cur : -1;
+    for (size_t v = 0; dst[c] < 0 && v < s->ver.size(); ++v) if (s->ver_ref[v] == 0) dst[c] = (int)v;
+    if (dst[c] < 0) return RV_E_STASH_FULL;
+  }
+  hipStream_t st = stages[0]->st;
+  const rv_stage* p = pending >= 0 ? stages[pending] : nullptr;
+  RV_TRY(rv_cluster_average(masters, C, stages[0]->P, R, nullptr, 1, p ? p->grad : nullptr, pending >= 0 ? pending : 0,
+                            p ? p->eta : 0.f, st));
+  for (int c = 0; c < C; ++c) {
+    rv_stage* s = stages[c];
+    RV_TRY(rv_launch_publish(s->master, s->P, s->ver[dst[c]], copy_kind(s), st));
+    s->cur = dst[c];
+  }
+  return RV_OK;
+}
+
 extern "C" rv_status rv_stage_get_params(const rv_stage* s, float* flat_out, size_t n) {
   if (!s || !flat_out || n != s->P) return RV_E_INVAL;
   RV_HIP_TRY(hipMemcpyAsync(flat_out, s->master, n * 4, hipMemcpyDeviceToDevice, s->st));
@@ -155,6 +192,7 @@ extern "C" rv_status rv_stage_last_grad(const rv_stage* s, float* flat_out, size
 rv_status rv_stage_update_range(rv_stage* s, size_t off, size_t n, hipStream_t st) {
   const int kind = s->dtype == RV_BF16 ? 1 : 2;
   const float* g = s->grad + off;
+  if (s->defer) return RV_OK;   // the update stays pending
   if (s->accum > 1) {   // sum the group's gradients; only its last microbatch updates
     RV_TRY(rv_launch_accumulate(s->gacc + off, g, n, s->acc_count == 0, st));
     if (s->acc_count + 1 < s->accum) return RV_OK;
@@ -196,7 +234,7 @@ rv_status do_backward(rv_stage* s, int slot_i, const void* grad_out, void* grad_
   // this is safe even when the slot is the one this backward reads.
   // With gradient accumulation only the last microbatch of a group updates; the others leave
   // the current version in force.
-  const bool updates = s->acc_count + 1 >= s->accum;
+  const bool updates = !s->defer && s->acc_count + 1 >= s->accum;
   int dst = -1;
   auto refs = [&](size_t v) { return s->ver_ref[v] - ((int)v == sl.ver ? 1 : 0); };
   if (updates) {
@@ -218,7 +256,7 @@ rv_status do_backward(rv_stage* s, int slot_i, const void* grad_out, void* grad_
   s->ver_ref[sl.ver] -= 1;
   sl.ver = -1;
   if (updates) { s->cur = dst; s->acc_count = 0; }
-  else s->acc_count += 1;
+  else if (!s->defer) s->acc_count += 1;
   return RV_OK;
 }
 
