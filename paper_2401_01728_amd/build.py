@@ -19,6 +19,9 @@ GENLIB = os.path.join(HERE, "inputs", "librvgen.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # MFMA results that feed vector arithmetic (attention scores) stay in VGPRs instead of
+         # being parked in and copied back from the accumulator registers
+         "-mllvm", "-amdgpu-mfma-vgpr-form",
          "-Wno-unused-command-line-argument"]
 
 
