@@ -18,8 +18,9 @@
 //
 // Softmax runs in base 2: s2 = s * (log2(e)/sqrt(dh)), p = exp2(s2 - m).  The forward
 // stores lse2 = m + log2(sum); the backward recomputes p = exp2(s2 - lse2).
-// Backward is split in two deterministic kernels (no atomics): one accumulates dK and dV
-// per key tile over the queries that see it, one accumulates dQ per query tile.
+// Backward is split in two deterministic kernels (no atomics): one accumulates dQ per query
+// tile (and leaves D = rowsum(dO * O) behind), one accumulates dK and dV per key tile over the
+// queries that see it.
 #include "internal.h"
 
 namespace {
@@ -196,17 +197,25 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(const uint16_t* __re
           s[sub] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_kc<DH>(Ks, sub * 32, kk), qf[kk], s[sub], 0, 0, 0);
       // running max m is kept in the scaled base-2 domain; the scale (> 0) commutes with max,
       // so the row max is taken over raw scores and p = exp2(s*c2 - m) is one FMA + one exp
+      // only tiles that straddle the diagonal pay for the causal mask (wave-uniform branch)
       const bool diag = k0 + TILE - 1 > q0;
       float mx = -INFINITY;
+      if (diag) {
 #pragma unroll
-      for (int sub = 0; sub < 2; ++sub)
+        for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          float v = s[sub][r];
-          if (diag && k0 + sub * 32 + acc_row(r, grp) > qi) v = -INFINITY;
-          s[sub][r] = v;
-          mx = fmaxf(mx, v);
-        }
+          for (int r = 0; r < 16; ++r) {
+            float v = s[sub][r];
+            if (k0 + sub * 32 + acc_row(r, grp) > qi) v = -INFINITY;
+            s[sub][r] = v;
+            mx = fmaxf(mx, v);
+          }
+      } else {
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[sub][r]);
+      }
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
       const float mn = fmaxf(m, mx * c2);
       const float alpha = __builtin_amdgcn_exp2f(m - mn);
@@ -221,8 +230,11 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(const uint16_t* __re
           ps += p;
         }
       lsum = lsum * alpha + ps;
+      // once the running maxima have settled alpha is exactly 1 in every lane: skip the rescale
+      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f)) {
 #pragma unroll
-      for (int dt = 0; dt < DH / 32; ++dt) o[dt] *= alpha;
+        for (int dt = 0; dt < DH / 32; ++dt) o[dt] *= alpha;
+      }
 #pragma unroll
       for (int sub = 0; sub < 2; ++sub)
 #pragma unroll
@@ -246,35 +258,9 @@ __global__ __launch_bounds__(kThreads) void attn_fwd_kernel(const uint16_t* __re
   if (grp == 0) lse2[((int64_t)b * H + h) * S + qi] = m + __builtin_amdgcn_logf(tot);   // v_log_f32 is log2
 }
 
-// D[b,h,i] = sum_dh dO[i,dh] * O[i,dh]  (one lane group of 8 per row-head)
-template <int DH>
-__global__ void attn_rowdot_kernel(const uint16_t* __restrict__ o, const uint16_t* __restrict__ dout, int64_t ld,
-                                   float* __restrict__ D, int S, int H, int64_t total) {
-  const int64_t idx = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / 8;   // (token, head)
-  const int part = threadIdx.x & 7;
-  if (idx >= total) return;
-  const int64_t tok = idx / H; const int h = (int)(idx % H);
-  float acc = 0.f;
-#pragma unroll
-  for (int c = part * 8; c < DH; c += 64) {
-    u32x4 a = *reinterpret_cast<const u32x4*>(o + tok * ld + h * DH + c);
-    u32x4 g = *reinterpret_cast<const u32x4*>(dout + tok * ld + h * DH + c);
-    const unsigned av[4] = {a.x, a.y, a.z, a.w}, gv[4] = {g.x, g.y, g.z, g.w};
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      acc += __uint_as_float(av[k] << 16) * __uint_as_float(gv[k] << 16);
-      acc += __uint_as_float(av[k] & 0xFFFF0000u) * __uint_as_float(gv[k] & 0xFFFF0000u);
-    }
-  }
-  acc += __shfl_xor(acc, 1, 64); acc += __shfl_xor(acc, 2, 64); acc += __shfl_xor(acc, 4, 64);
-  if (part == 0) {
-    const int64_t b = tok / S; const int i = (int)(tok % S);
-    D[(b * H + h) * S + i] = acc;
-  }
-}
-
 // ----------------------------------------------------------------------------------------
-// backward, part 1: dK and dV.  A wave owns 32 keys (lane = key); queries stream.
+// backward, part 2 (launched second: it reads the D the dQ kernel stores): dK and dV.
+// A wave owns 32 keys (lane = key); queries stream.
 // ----------------------------------------------------------------------------------------
 template <int DH>
 __global__ __launch_bounds__(kThreads) void attn_bwd_kv_kernel(const uint16_t* __restrict__ qkv, int64_t ld,
@@ -345,14 +331,24 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kv_kernel(const uint16_t* _
           s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_kc<DH>(Qkc, sub * 32, kk), kf[kk], s, 0, 0, 0);
           dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_kc<DH>(Okc, sub * 32, kk), vf[kk], dp, 0, 0, 0);
         }
-        const bool diag = is < j0 + WROWS - 1;
+        const bool diag = is < j0 + WROWS - 1;           // wave-uniform: only diagonal tiles mask
+        if (diag) {
 #pragma unroll
-        for (int rr = 0; rr < 16; ++rr) {
-          const int il = sub * 32 + acc_row(rr, grp);     // query row inside the tile
-          float p = __builtin_amdgcn_exp2f(s[rr] * c2 - stat[il]);
-          if (diag && ji > i0 + il) p = 0.f;
-          s[rr] = p;
-          dp[rr] = p * (dp[rr] - stat[TILE + il]);
+          for (int rr = 0; rr < 16; ++rr) {
+            const int il = sub * 32 + acc_row(rr, grp);     // query row inside the tile
+            float p = __builtin_amdgcn_exp2f(__fmaf_rn(s[rr], c2, -stat[il]));
+            if (ji > i0 + il) p = 0.f;
+            s[rr] = p;
+            dp[rr] = p * (dp[rr] - stat[TILE + il]);
+          }
+        } else {
+#pragma unroll
+          for (int rr = 0; rr < 16; ++rr) {
+            const int il = sub * 32 + acc_row(rr, grp);
+            const float p = __builtin_amdgcn_exp2f(__fmaf_rn(s[rr], c2, -stat[il]));
+            s[rr] = p;
+            dp[rr] = p * (dp[rr] - stat[TILE + il]);
+          }
         }
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
@@ -377,13 +373,14 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kv_kernel(const uint16_t* _
 }
 
 // ----------------------------------------------------------------------------------------
-// backward, part 2: dQ.  A wave owns 32 queries (lane = query); keys stream.
+// backward, part 1: dQ, and D = rowsum(dO * O).  A wave owns 32 queries (lane = query); keys stream.
 // ----------------------------------------------------------------------------------------
 template <int DH>
 __global__ __launch_bounds__(kThreads) void attn_bwd_q_kernel(const uint16_t* __restrict__ qkv, int64_t ld,
                                                               const uint16_t* __restrict__ dout, int64_t ldo,
+                                                              const uint16_t* __restrict__ outp,
                                                               const float* __restrict__ lse2,
-                                                              const float* __restrict__ Dv,
+                                                              float* __restrict__ Dv,
                                                               uint16_t* __restrict__ dqkv, int S, int d, int H,
                                                               int nseq, float c2, float scale) {
   extern __shared__ __align__(16) char smem[];
@@ -409,7 +406,21 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_q_kernel(const uint16_t* __
     load_owned<DH>(qf, qkv + (tok0 + q0) * ld + h * DH, ld);
     load_owned<DH>(of, dout + (tok0 + q0) * ldo + h * DH, ldo);
     lse_i = lse2[((int64_t)b * H + h) * S + qi];
-    D_i = Dv[((int64_t)b * H + h) * S + qi];
+    // D_i = sum_dh dO[i,dh] * O[i,dh]: the wave holds its rows of dO as fragments already; the
+    // rows of O come in the same layout.  Stored for the dK/dV kernel, which runs after this one.
+    bf16x8 oo[DH / 16];
+    load_owned<DH>(oo, outp + (tok0 + q0) * ldo + h * DH, ldo);
+#pragma unroll
+    for (int kk = 0; kk < DH / 16; ++kk) {
+      const u32x4 a = __builtin_bit_cast(u32x4, oo[kk]), g = __builtin_bit_cast(u32x4, of[kk]);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        D_i = __fmaf_rn(__uint_as_float(a[e] << 16), __uint_as_float(g[e] << 16), D_i);
+        D_i = __fmaf_rn(__uint_as_float(a[e] & 0xFFFF0000u), __uint_as_float(g[e] & 0xFFFF0000u), D_i);
+      }
+    }
+    D_i += __shfl_xor(D_i, 32, 64);
+    if (grp == 0) Dv[((int64_t)b * H + h) * S + qi] = D_i;
   }
   f32x16 dq[DH / 32];
 #pragma unroll
@@ -441,12 +452,18 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_q_kernel(const uint16_t* __
           s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_kc<DH>(Kkc, sub * 32, kk), qf[kk], s, 0, 0, 0);
           dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag_kc<DH>(Vkc, sub * 32, kk), of[kk], dp, 0, 0, 0);
         }
-        const bool diag = ks0 + 31 > q0;
+        const bool diag = ks0 + 31 > q0;                  // wave-uniform: only diagonal tiles mask
+        if (diag) {
 #pragma unroll
-        for (int rr = 0; rr < 16; ++rr) {
-          float p = __builtin_amdgcn_exp2f(s[rr] * c2 - lse_i);
-          if (diag && ks0 + acc_row(rr, grp) > qi) p = 0.f;
-          dp[rr] = p * (dp[rr] - D_i);
+          for (int rr = 0; rr < 16; ++rr) {
+            float p = __builtin_amdgcn_exp2f(__fmaf_rn(s[rr], c2, -lse_i));
+            if (ks0 + acc_row(rr, grp) > qi) p = 0.f;
+            dp[rr] = p * (dp[rr] - D_i);
+          }
+        } else {
+#pragma unroll
+          for (int rr = 0; rr < 16; ++rr)
+            dp[rr] = __builtin_amdgcn_exp2f(__fmaf_rn(s[rr], c2, -lse_i)) * (dp[rr] - D_i);
         }
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
@@ -507,27 +524,23 @@ rv_status rv_attn_bwd(const uint16_t* qkv, const uint16_t* out, const uint16_t* 
   const int dh = d / H;
   const float scale = 1.0f / sqrtf((float)dh);
   const float c2 = 1.4426950408889634f * scale;
-  const int64_t total = (int64_t)mb * S * H;
   const int nwg = ((S + BROWS - 1) / BROWS) * H * mb;
   dim3 grid(nwg);
-  const unsigned rd_blocks = (unsigned)((total * 8 + 255) / 256);
   if (dh == 64) {
     constexpr int s1 = 2 * (L<64>::KC_BYTES + L<64>::KM_BYTES) + 2 * TILE * 4;
     constexpr int s2 = 2 * L<64>::KC_BYTES + L<64>::KM_BYTES;
     RV_TRY(set_smem(attn_bwd_kv_kernel<64>, s1)); RV_TRY(set_smem(attn_bwd_q_kernel<64>, s2));
-    hipLaunchKernelGGL(attn_rowdot_kernel<64>, dim3(rd_blocks), dim3(256), 0, st, out, dout, (int64_t)d, Dbuf, S, H, total);
-    hipLaunchKernelGGL(attn_bwd_kv_kernel<64>, grid, dim3(kThreads), s1, st, qkv, (int64_t)3 * d, dout, (int64_t)d,
-                       lse2, Dbuf, dqkv, S, d, H, mb, c2, scale);
     hipLaunchKernelGGL(attn_bwd_q_kernel<64>, grid, dim3(kThreads), s2, st, qkv, (int64_t)3 * d, dout, (int64_t)d,
+                       out, lse2, Dbuf, dqkv, S, d, H, mb, c2, scale);
+    hipLaunchKernelGGL(attn_bwd_kv_kernel<64>, grid, dim3(kThreads), s1, st, qkv, (int64_t)3 * d, dout, (int64_t)d,
                        lse2, Dbuf, dqkv, S, d, H, mb, c2, scale);
   } else {
     constexpr int s1 = 2 * (L<128>::KC_BYTES + L<128>::KM_BYTES) + 2 * TILE * 4;
     constexpr int s2 = 2 * L<128>::KC_BYTES + L<128>::KM_BYTES;
     RV_TRY(set_smem(attn_bwd_kv_kernel<128>, s1)); RV_TRY(set_smem(attn_bwd_q_kernel<128>, s2));
-    hipLaunchKernelGGL(attn_rowdot_kernel<128>, dim3(rd_blocks), dim3(256), 0, st, out, dout, (int64_t)d, Dbuf, S, H, total);
-    hipLaunchKernelGGL(attn_bwd_kv_kernel<128>, grid, dim3(kThreads), s1, st, qkv, (int64_t)3 * d, dout, (int64_t)d,
-                       lse2, Dbuf, dqkv, S, d, H, mb, c2, scale);
     hipLaunchKernelGGL(attn_bwd_q_kernel<128>, grid, dim3(kThreads), s2, st, qkv, (int64_t)3 * d, dout, (int64_t)d,
+                       out, lse2, Dbuf, dqkv, S, d, H, mb, c2, scale);
+    hipLaunchKernelGGL(attn_bwd_kv_kernel<128>, grid, dim3(kThreads), s1, st, qkv, (int64_t)3 * d, dout, (int64_t)d,
                        lse2, Dbuf, dqkv, S, d, H, mb, c2, scale);
   }
   return rv_launch_status();
