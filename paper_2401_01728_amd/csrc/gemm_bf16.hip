@@ -41,31 +41,32 @@ __host__ __device__ constexpr int tile_bytes(bool km, int rows, int bk) {
   return km ? bk * pitch_km(rows) : rows * pitch_kc(bk);
 }
 
-// GELU(z) = z * Phi(z) and its derivative Phi(z) + z * phi(z), with the normal CDF from the
-// rational-exponential form of erf (Abramowitz & Stegun 7.1.26, |error| < 1.5e-7): the tail
-// Q = 1 - Phi(|z|) = 0.5 * poly(t) * exp(-z^2/2), t = 1/(1 + p |z|/sqrt(2)), is computed
-// directly, so negative arguments lose no digits to cancellation.  The same exponential
-// serves phi(z).  About a dozen instructions instead of a library erf.
-__device__ __forceinline__ void phi_parts(float z, float& cdf, float& e) {
-  const float x = fabsf(z) * 0.70710678118654752f;
-  const float t = __builtin_amdgcn_rcpf(__fmaf_rn(0.3275911f, x, 1.0f));
-  e = __expf(-x * x);
-  float p = __fmaf_rn(1.061405429f, t, -1.453152027f);
-  p = __fmaf_rn(p, t, 1.421413741f);
-  p = __fmaf_rn(p, t, -0.284496736f);
-  p = __fmaf_rn(p, t, 0.254829592f);
-  const float q = 0.5f * p * t * e;          // upper tail of |z|
-  cdf = z < 0.f ? q : 1.0f - q;
+// GELU(z) = z * Phi(z) and its derivative Phi(z) + z * phi(z).  The upper tail of the normal
+// distribution, q = 1 - Phi(|z|) = erfc(|z|/sqrt 2)/2, comes from the three-term
+// rational-exponential form of erfc (Abramowitz & Stegun 7.1.25, |error| < 1.3e-5 on q - the
+// results are rounded to bf16, whose half-ulp is 2e-3 relative):
+//   q = (a1 t + a2 t^2 + a3 t^3)/2 * exp(-z^2/2),   t = 1/(1 + 0.47047 |z|/sqrt 2).
+// Computing the tail directly loses no digits to cancellation for negative arguments, and
+//   GELU(z) = max(z, 0) - |z| q
+// needs no select.  The same exponential serves phi(z).  Nine instructions, two of them
+// transcendental.
+__device__ __forceinline__ float tail_q(float z, float& e) {
+  const float t = __builtin_amdgcn_rcpf(__fmaf_rn(fabsf(z), 0.33267254f, 1.0f));
+  e = __builtin_amdgcn_exp2f(z * z * -0.72134752f);
+  float p = __fmaf_rn(0.3739278f, t, -0.0479399f);
+  p = __fmaf_rn(p, t, 0.1740121f);
+  return p * t * e;
 }
 __device__ __forceinline__ float gelu_f(float z) {
-  float c, e;
-  phi_parts(z, c, e);
-  return z * c;
+  float e;
+  const float q = tail_q(z, e);
+  return __fmaf_rn(-fabsf(z), q, fmaxf(z, 0.f));
 }
 __device__ __forceinline__ float dgelu_f(float z) {
-  float c, e;
-  phi_parts(z, c, e);
-  return __fmaf_rn(z * 0.3989422804014327f, e, c);
+  float e;
+  const float q = tail_q(z, e);
+  const float cdf = z < 0.f ? q : 1.0f - q;
+  return __fmaf_rn(z * 0.3989422804014327f, e, cdf);
 }
 
 // ---- global -> registers ---------------------------------------------------------------
@@ -351,6 +352,19 @@ __device__ __forceinline__ void write_tile_staged(const f32x16 (&acc)[TM][TN], c
   constexpr int PASSES = EPI == EPI_BF16_BIAS_GELU ? 2 : 1;
   const int l = threadIdx.x & 63;
   __syncthreads();   // every wave has finished reading operands from the ring
+  if (EPI == EPI_BF16_DGELU) {
+    // the pre-activation tile comes in the way the result goes out: whole rows, 16 bytes per
+    // lane, through the image; a lane then finds its own four values where it will put the result
+    constexpr int CPR = BN / 8;
+    for (int idx = threadIdx.x; idx < BM * CPR; idx += NT) {
+      const int row = idx / CPR, c = idx % CPR;
+      const int gm = m0 + row, gn = n0 + c * 8;
+      if (gm < M && gn < N)
+        *reinterpret_cast<u32x4*>(smem + row * PITCH + c * 16) =
+            *reinterpret_cast<const u32x4*>(e.zin + (int64_t)gm * e.ldo + gn);
+    }
+    __syncthreads();
+  }
 #pragma unroll
   for (int pass = 0; pass < PASSES; ++pass) {
 #pragma unroll
@@ -373,7 +387,7 @@ __device__ __forceinline__ void write_tile_staged(const f32x16 (&acc)[TM][TN], c
           }
           if (EPI == EPI_BF16_DGELU) {
             if (gm < M && gn < N) {
-              u32x2 z = *reinterpret_cast<const u32x2*>(e.zin + (int64_t)gm * e.ldo + gn);
+              const u32x2 z = *reinterpret_cast<const u32x2*>(smem + ml * PITCH + nl * 2);
               a.x *= dgelu_f(__uint_as_float(z.x << 16)); a.y *= dgelu_f(__uint_as_float(z.x & 0xFFFF0000u));
               a.z *= dgelu_f(__uint_as_float(z.y << 16)); a.w *= dgelu_f(__uint_as_float(z.y & 0xFFFF0000u));
             }
