@@ -36,8 +36,11 @@ __device__ __forceinline__ u32x2 f32_to_bf16x4(f32x4 a) {
 
 // y = LN(x) * gamma + beta.  IN_BF16: x arrives as bf16 (stage input) and is also written
 // out as the fp32 residual stream xcopy.
+// Four waves of at most 80 registers (NV <= 8) and no LDS: such a workgroup still finds room on a
+// CU whose registers are mostly held by two 200-register waves per SIMD of a matrix-product
+// kernel of another stream, so the HBM-bound LayerNorm can run under the MFMA-bound products.
 template <int NV, bool IN_BF16>
-__global__ __launch_bounds__(kThreads, NV <= 4 ? 4 : 1) void ln_fwd_kernel(const void* __restrict__ xin,
+__global__ __launch_bounds__(kThreads, NV <= 8 ? 6 : 1) void ln_fwd_kernel(const void* __restrict__ xin,
                                                           float* __restrict__ xcopy,
                                                           const uint16_t* __restrict__ gamma,
                                                           const uint16_t* __restrict__ beta,
@@ -94,15 +97,18 @@ __global__ __launch_bounds__(kThreads, NV <= 4 ? 4 : 1) void ln_fwd_kernel(const
 //   0: sum dy * xh (d gamma)   1: sum dy (d beta)   2: sum dx (bias gradient of the Linear
 //   whose output fed this residual stream).
 constexpr int kRowsPerBlock = 16;
-constexpr int kBwdWaves = 8;
+constexpr int kBwdWaves = 4;
 
-// Eight waves per workgroup.  A row is split over CS waves (CS = 1, 2, 4 for d <= 1024,
-// 2048, 4096) so that a lane never owns more than four 16-byte column groups: the three
-// column accumulators and the row operands stay in ~170 registers for every width.  The
-// 8/CS wave groups take rows round-robin; with CS > 1 the row statistics are combined
-// through LDS (fixed order, one barrier per row, two alternating slots).
-template <int CS>
-__global__ __launch_bounds__(64 * kBwdWaves) void ln_bwd_kernel(const uint16_t* __restrict__ dy,
+// Four waves per workgroup.  A row is split over CS waves, a lane owning NV 16-byte column
+// groups of it: NV = 2 and CS = 1, 2, 4 for d <= 512, 1024, 2048 keep the three column
+// accumulators and the row operands within 80 registers - one such wave per SIMD and at most
+// 16 KiB of LDS fit beside the two 200-register waves of a matrix-product kernel of another
+// stream, so the HBM-bound backward runs under the MFMA-bound products instead of waiting for
+// a free CU.  Wider rows take NV = 4, CS = 4.  The 4/CS wave groups take rows round-robin;
+// with CS > 1 the row statistics are combined through LDS (fixed order, one barrier per row,
+// two alternating slots).
+template <int CS, int NV>
+__global__ __launch_bounds__(64 * kBwdWaves, NV <= 2 ? 6 : 1) void ln_bwd_kernel(const uint16_t* __restrict__ dy,
                                                                 const float* __restrict__ x,
                                                                 const float* __restrict__ mean,
                                                                 const float* __restrict__ rstd,
@@ -110,12 +116,12 @@ __global__ __launch_bounds__(64 * kBwdWaves) void ln_bwd_kernel(const uint16_t* 
                                                                 const float* dres, float* dx,
                                                                 uint16_t* __restrict__ dx_bf16,
                                                                 float* __restrict__ part, int T, int d) {
-  constexpr int NV = 4, RG = kBwdWaves / CS;
+  constexpr int RG = kBwdWaves / CS;
   extern __shared__ __align__(16) float red[];   // [RG][d] column sums, then [2][RG][CS][2] row statistics
   float* stat = red + RG * d;
   const int wave = threadIdx.x >> 6, l = threadIdx.x & 63;
   const int cs = wave % CS, rg = wave / CS;
-  const int cbase = cs * 1024 + l * 4;
+  const int cbase = cs * (NV * 256) + l * 4;
   f32x4 ag[NV], ab[NV], ax[NV];
 #pragma unroll
   for (int i = 0; i < NV; ++i) { ag[i] = 0.f; ab[i] = 0.f; ax[i] = 0.f; }
@@ -294,15 +300,14 @@ rv_status rv_ln_bwd(const uint16_t* dy, const float* x, const float* mean, const
   if (!dy || !x || !mean || !rstd || !gamma || !dres || !dx || !part || T < 1 || d < 4 || d % 4 || d > 4096)
     return RV_E_INVAL;
   dim3 grid(rv_ln_bwd_parts(T)), blk(64 * kBwdWaves);
-  const int cs = d <= 1024 ? 1 : d <= 2048 ? 2 : 4;
+  const int cs = d <= 512 ? 1 : d <= 1024 ? 2 : 4;
   const size_t smem = ((size_t)(kBwdWaves / cs) * d + 2 * kBwdWaves * 2) * sizeof(float);
-#define RV_LN_BWD(CS) \
-  hipLaunchKernelGGL((ln_bwd_kernel<CS>), grid, blk, smem, st, dy, x, mean, rstd, gamma, dres, dx, dx_bf16, part, T, d);
-  switch (cs) {
-    case 1: RV_LN_BWD(1) break;
-    case 2: RV_LN_BWD(2) break;
-    default: RV_LN_BWD(4) break;
-  }
+#define RV_LN_BWD(CS, NV) \
+  hipLaunchKernelGGL((ln_bwd_kernel<CS, NV>), grid, blk, smem, st, dy, x, mean, rstd, gamma, dres, dx, dx_bf16, part, T, d);
+  if (d <= 512) { RV_LN_BWD(1, 2) }
+  else if (d <= 1024) { RV_LN_BWD(2, 2) }
+  else if (d <= 2048) { RV_LN_BWD(4, 2) }
+  else { RV_LN_BWD(4, 4) }
 #undef RV_LN_BWD
   return rv_launch_status();
 }
