@@ -96,7 +96,7 @@ __global__ __launch_bounds__(kThreads, NV <= 8 ? 6 : 1) void ln_fwd_kernel(const
 // column sums over the workgroup's rows into part[blk][0..2][d]:
 //   0: sum dy * xh (d gamma)   1: sum dy (d beta)   2: sum dx (bias gradient of the Linear
 //   whose output fed this residual stream).
-constexpr int kRowsPerBlock = 16;
+constexpr int kRowsPerBlock = 8;
 constexpr int kBwdWaves = 4;
 
 // Four waves per workgroup.  A row is split over CS waves, a lane owning NV 16-byte column
