@@ -3,7 +3,8 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME]
 
-Workloads (synthetic, seeded; see the design doc for the recipes):
+Workloads (synthetic, seeded: activations N(0,1) and upstream gradients N(0,1e-3) rounded to bf16,
+parameters N(0,0.02) with LayerNorm gains 1+N(0,0.02); replicas x_c = o + n_c with o, n_c ~ N(0,1)):
   stage2  (default) the middle transformer-decoder stage: 4 pre-LN blocks, d_model 1024,
           16 heads, FFN 4096, seq 512, microbatch 8, tau 2.  A step is the steady-state
           stage step: forward(t), backward(t - tau), delayed SGD update.  tokens/s.

@@ -149,8 +149,10 @@ rv_status rv_stage_backward(rv_stage* s, int64_t mb_id, const void* grad_out, vo
  * calling them in that order: the forward runs at the parameters in force BEFORE this
  * step's update (it does not wait for the gradient of bwd_mb - the zero-bubble property
  * of section 3.1), the backward at the version stashed for bwd_mb, then the update of
- * Eq. 2.  The two halves are independent and are enqueued on two streams (the stage's
- * stream and an internal one, forked and joined with events), so their kernels overlap on
+ * Eq. 2.  The two halves are independent and are enqueued on separate streams (the forward on
+ * the stage's stream; the backward's chain dy -> dx on an internal one; its parameter-gradient
+ * work - weight-gradient products, bias and LayerNorm reductions, the block-by-block update -
+ * on a third; forked and joined with events, default priorities), so their kernels overlap on
  * the GPU; all work is ordered after what was on the stage's stream at the call and before
  * what is enqueued on it afterwards.  With fwd_mb == bwd_mb (tau = 0) the halves run in
  * sequence.  Errors as for the two calls; RV_E_STASH_FULL if no slot is free for fwd_mb.
