@@ -121,3 +121,39 @@ def test_config4_sampled(R):
     ref = X.astype(np.float64).mean(axis=0)               # xs[gr] already holds the folded step (fp32 inputs)
     bound = 1e-6 * (np.abs(X).astype(np.float64).mean(axis=0) + eta * np.abs(gh) / C)
     assert np.all(np.abs(got.astype(np.float64) - ref) <= bound + 1e-6 * np.abs(step) / C)
+
+
+@pytest.mark.parametrize("name,L,d,H,f,S,mb,tau", [("config2", 4, 1024, 16, 4096, 512, 8, 2),
+                                                   ("config5 (4 of 12 blocks)", 4, 1600, 25, 6400, 1024, 8, 4)])
+def test_fused_steps_at_bench_shapes_are_bitwise_the_sequential_calls(name, L, d, H, f, S, mb, tau):
+    """rv_stage_step as bench.py times it (forward, backward chain and parameter-gradient work on
+    three streams, buffers alternating between blocks) must give, bit for bit, what the same
+    schedule gives as forward(t); backward(t - tau) on one stream - at the real shapes, where a
+    missing dependency between the streams would show."""
+    import paper_2401_01728_amd as rv
+    from paper_2401_01728_amd.inputs import device
+    w0 = dev(decoder_params_host(2, L, d, f))
+    n = tau + 5
+    xs = [device.fill_normal_(torch.empty(mb, S, d, dtype=torch.bfloat16, device="cuda"), 2, 1000 + t) for t in range(n)]
+    dys = [device.fill_normal_(torch.empty(mb, S, d, dtype=torch.bfloat16, device="cuda"), 2, 2000 + t, 0.0, 1e-3)
+           for t in range(n)]
+    res = []
+    for fused in (False, True):
+        g = rv.Stage.decoder(L, d, H, f, S, mb, tau, 1e-3); g.set_params(w0)
+        outs = []
+        for t in range(n + tau):
+            j = t - tau
+            if fused and t < n and j >= 0:
+                y, dx = g.step(t, xs[t], j, dys[j]); outs += [y.clone(), dx.clone()]
+            else:
+                if t < n:
+                    outs.append(g.forward(t, xs[t]).clone())
+                if j >= 0:
+                    outs.append(g.backward(j, dys[j]).clone())
+        outs.append(g.get_params().clone()); outs.append(g.last_grad().clone())
+        torch.cuda.synchronize()
+        res.append(outs)
+        del g
+    assert len(res[0]) == len(res[1])
+    for k, (a, b) in enumerate(zip(*res)):
+        assert torch.equal(a, b), (name, k)
