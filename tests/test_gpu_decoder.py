@@ -150,15 +150,20 @@ def test_decoder_error_paths():
     assert g.in_flight == 0
 
 
-def test_decoder_stage_with_accumulation_in_fused_steps():
-    """Gradient accumulation (section 4.2) through rv_stage_step: block-wise accumulate / update on
-    the side stream, forwards bound to a version that only every second backward replaces."""
+@pytest.mark.parametrize("A,momentum,wd", [(2, 0.0, 0.0), (1, 0.9, 5e-4), (2, 0.9, 5e-4)])
+def test_decoder_stage_with_accumulation_in_fused_steps(A, momentum, wd):
+    """Gradient accumulation (section 4.2) and the momentum / weight-decay optimiser (section 4.1)
+    through rv_stage_step: block-wise accumulate / update on the side stream, forwards bound to
+    a version that only every A-th backward replaces."""
     import paper_2401_01728_amd as rv
-    L, d, H, f, S, mb, tau, A, eta = 2, 128, 2, 256, 128, 2, 2, 2, 1e-2
+    L, d, H, f, S, mb, tau, eta = 2, 128, 2, 256, 128, 2, 2, 1e-2
     shapes = blocks.decoder_param_shapes(L, d, f)
     w0 = decoder_params_host(31, L, d, f)
     g = rv.Stage.decoder(L, d, H, f, S, mb, tau, eta); g.set_params(dev(w0)); g.set_accumulation(A)
-    o = ostage.Stage("decoder", tau, eta, w0, n_blocks=L, d=d, h=H, f=f, accumulate=A)
+    if momentum or wd:
+        g.set_optimizer(momentum, wd)
+    o = ostage.Stage("decoder", tau, eta, w0, n_blocks=L, d=d, h=H, f=f, accumulate=A, momentum=momentum,
+                     weight_decay=wd)
     n = 7
     for t in range(n + tau):
         j = t - tau
