@@ -103,7 +103,10 @@ def bench_avg4(args):
            "value": gbs, "unit": "GB/s", "ms_per_step": ms, "dtype": "f32",
            "config": {"workload": "avg4: N=%d fp32, C=16, R=%d, fused grad" % (n, R)},
            "roofline": {"bound": "hbm", "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                        "frac": gbs / HBM_PEAK_GBS, "traffic": None, "kernel": "average_kernel<16,true>",
+                        "frac": gbs / HBM_PEAK_GBS,
+                        # counter runs recorded in profiles/avg4_average_kernel.md (default N, R = 4 only)
+                        "traffic": 72.0e9 if (n == 1_000_000_000 and R == 4) else None,
+                        "kernel": "average_kernel<16,true>",
                         "algorithmic_bytes_per_launch": alg_bytes}}
     if not args.no_cpu:
         res["cpu_baseline"] = cpu_average(C, R, eta, seed)
