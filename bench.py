@@ -204,7 +204,7 @@ def bench_stage(args, name):
     # bytes per launch through the L2s' fabric ports, from the rocprofv3 counter runs recorded in
     # profiles/stage2_stage_step_kernel_trace.md (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the factors a
     # plain copy of known size gives); measured for the config-2 shapes only
-    traffic = 470.1e6 if name == "stage2" else None
+    traffic = 268.7e6 if name == "stage2" else None
     res["roofline"] = {"bound": "mfma", "achieved": kfl / (kms * 1e-3) / 1e12, "peak": BF16_PEAK_TFLOPS,
                        "unit": "TFLOP/s", "frac": kfl / (kms * 1e-3) / 1e12 / BF16_PEAK_TFLOPS, "traffic": traffic,
                        "kernel": "gemm_dtl_grouped_wgrad_kernel (dW2, dW1, dWo, dWqkv of one block, K=%d tokens)" % T,

@@ -600,7 +600,7 @@ __global__ __launch_bounds__(64 * NW, WPE) void gemm_dtl_kernel(const uint16_t* 
 // One launch fills the chip where four small grids would each leave most CUs idle.
 struct GroupedProblem {
   const uint16_t* A; const uint16_t* B; float* out;
-  int lda, ldb, ldo, M, N, K, tiles_m, first_tile;
+  int lda, ldb, ldo, M, N, K, tiles_m, tiles_n, first_tile;
 };
 struct GroupedArgs {
   GroupedProblem p[RV_GEMM_GROUP_MAX];
@@ -609,15 +609,25 @@ struct GroupedArgs {
 
 template <int BM, int BN, int BK, int NS, int NW, int WPE>
 __global__ __launch_bounds__(64 * NW, WPE) void gemm_dtl_grouped_wgrad_kernel(GroupedArgs ga) {
+  // Workgroup ids are dealt to the 8 XCDs in turn, and each XCD pulls its operand panels
+  // through its own L2.  Give XCD g a CONTIGUOUS range of the tile numbering (so it works on
+  // one problem at a time, not on a slice of all of them) and number a problem's tiles in bands
+  // of two tile rows, column by column (so a run of 8 tiles is a 2 x 4 patch: 6 operand panels).
+  const int total = gridDim.x, base = total / 8, rem = total % 8;
+  const int g = blockIdx.x % 8, i = blockIdx.x / 8;
+  const int v = g * base + (g < rem ? g : rem) + i;
   int pi = 0;
 #pragma unroll
   for (int k = 1; k < RV_GEMM_GROUP_MAX; ++k)
-    if (k < ga.count && (int)blockIdx.x >= ga.p[k].first_tile) pi = k;
+    if (k < ga.count && v >= ga.p[k].first_tile) pi = k;
   const GroupedProblem& q = ga.p[pi];
-  const int local = blockIdx.x - q.first_tile;
+  const int local = v - q.first_tile;
+  const int band = local / (2 * q.tiles_n), first_row = band * 2;
+  const int rows = q.tiles_m - first_row < 2 ? q.tiles_m - first_row : 2;
+  const int in = local - band * 2 * q.tiles_n;
   Epi e{q.out, q.ldo, nullptr, nullptr, nullptr, 0, nullptr, nullptr};
-  gemm_dtl_body<BM, BN, BK, NS, NW, true, true, EPI_F32>(q.A, q.lda, q.B, q.ldb, q.M, q.N, q.K, local % q.tiles_m,
-                                                      local / q.tiles_m, e);
+  gemm_dtl_body<BM, BN, BK, NS, NW, true, true, EPI_F32>(q.A, q.lda, q.B, q.ldb, q.M, q.N, q.K, first_row + in % rows,
+                                                      in / rows, e);
 }
 
 template <int BM, int BN, int BK, int NS, int NW, int WPE, bool AKM, bool BKM, int EPI>
@@ -743,8 +753,9 @@ rv_status launch_grouped(const rv_gemm_args* gs, int count, hipStream_t st) {
     q.A = g.A; q.B = g.B; q.out = (float*)g.out;
     q.lda = (int)g.lda; q.ldb = (int)g.ldb; q.ldo = (int)g.ldo; q.M = g.M; q.N = g.N; q.K = g.K;
     q.tiles_m = (g.M + BM - 1) / BM;
+    q.tiles_n = (g.N + BN - 1) / BN;
     q.first_tile = tiles;
-    tiles += q.tiles_m * ((g.N + BN - 1) / BN);
+    tiles += q.tiles_m * q.tiles_n;
   }
   for (int k = count; k < RV_GEMM_GROUP_MAX; ++k) ga.p[k] = ga.p[0];
   ga.count = count;
