@@ -92,6 +92,19 @@ rv_status rv_k_attention_bwd(const void* qkv, const void* out, const void* dout,
                              float* dscratch, void* dqkv, int microbatch, int seq, int d_model,
                              int n_heads, void* stream);
 
+/*
+ * rv_k_attention_bwd for callers that cannot allocate or own a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels, with the
+ * per-row scratch (one float per (microbatch, head, position)) in a fixed 1 MiB device array
+ * inside the library instead of `dscratch`.  The call allocates and frees nothing.
+ * RV_E_INVAL when microbatch * n_heads * seq > 262144, and on the shapes rv_k_attention_bwd
+ * rejects.  All calls on one GPU share that array: calls that overlap on one GPU (different
+ * streams, or threads) race; calls on one stream are ordered and need no clearing in between.
+ */
+rv_status rv_k_attention_bwd_static(const void* qkv, const void* out, const void* dout, const float* lse2,
+                                    void* dqkv, int microbatch, int seq, int d_model, int n_heads,
+                                    void* stream);
+
 #ifdef __cplusplus
 }
 #endif

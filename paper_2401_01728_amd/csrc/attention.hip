@@ -21,6 +21,7 @@
 // Backward is split in two deterministic kernels (no atomics): one accumulates dQ per query
 // tile (and leaves D = rowsum(dO * O) behind), one accumulates dK and dV per key tile over the
 // queries that see it.
+#include <mutex>
 #include "internal.h"
 
 namespace {
@@ -556,5 +557,46 @@ extern "C" rv_status rv_k_attention_bwd(const void* qkv, const void* out, const 
                                         float* dscratch, void* dqkv, int microbatch, int seq, int d_model,
                                         int n_heads, void* stream) {
   return rv_attn_bwd((const uint16_t*)qkv, (const uint16_t*)out, (const uint16_t*)dout, lse2, dscratch,
+                     (uint16_t*)dqkv, microbatch, seq, d_model, n_heads, (hipStream_t)stream);
+}
+
+// ---- the backward for callers that cannot allocate ---------------------------------------
+// The per-row term D = rowsum(dO * O) that the two backward kernels exchange lives in a
+// file-scope device array instead of a caller workspace.  Every GPU holds its own copy of
+// the array; its address on a device is looked up once, with that device current.
+namespace {
+constexpr int kStaticRows = 262144;   // 1 MiB: microbatch * n_heads * seq may not exceed this
+static __device__ __align__(256) float scratch[kStaticRows];
+constexpr int kMaxDevices = 64;
+float* g_scratch_ptr[kMaxDevices] = {};   // per device, filled on first use
+std::mutex g_scratch_mu;
+
+rv_status static_scratch(float** out) {
+  int dev = -1;
+  RV_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return RV_E_INVAL;
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    float* p = nullptr;
+    RV_HIP_TRY(hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)));
+    if (!p) return RV_E_DEVICE;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return RV_OK;
+}
+}  // namespace
+
+extern "C" rv_status rv_k_attention_bwd_static(const void* qkv, const void* out, const void* dout,
+                                               const float* lse2, void* dqkv, int microbatch, int seq,
+                                               int d_model, int n_heads, void* stream) {
+  if (microbatch < 1 || seq < 1 || n_heads < 1 ||
+      (int64_t)microbatch * n_heads * seq > (int64_t)kStaticRows)
+    return RV_E_INVAL;   // beyond the fixed scratch
+  float* D = nullptr;
+  RV_TRY(static_scratch(&D));
+  // every row of D that the second kernel reads is written by the first one in this call:
+  // nothing of the previous call's contents is used, so nothing has to be cleared
+  return rv_attn_bwd((const uint16_t*)qkv, (const uint16_t*)out, (const uint16_t*)dout, lse2, D,
                      (uint16_t*)dqkv, microbatch, seq, d_model, n_heads, (hipStream_t)stream);
 }

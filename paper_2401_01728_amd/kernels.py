@@ -74,3 +74,10 @@ def attention_bwd(qkv, out, dout, lse2, mb, S, d, H, stream=None):
     _check(_lib.lib().rv_k_attention_bwd(_ptr(qkv), _ptr(out), _ptr(dout), _ptr(lse2), _ptr(scratch), _ptr(dqkv),
                                          mb, S, d, H, _stream_handle(stream)))
     return dqkv
+
+
+def attention_bwd_static(qkv, out, dout, lse2, dqkv, mb, S, d, H, stream=None):
+    """rv_k_attention_bwd_static: dqkv is the caller's output; nothing is allocated here or in the library."""
+    _check(_lib.lib().rv_k_attention_bwd_static(_ptr(qkv), _ptr(out), _ptr(dout), _ptr(lse2), _ptr(dqkv), mb, S, d,
+                                                H, _stream_handle(stream)))
+    return dqkv
