@@ -40,6 +40,8 @@ SYMBOLS = {
                                    c_void_p, c_int, c_float, c_void_p]),
     "rv_cluster_average_v": (c_int, [ctypes.POINTER(c_void_p), c_int, c_size_t, ctypes.POINTER(c_int64), c_int,
                                      c_void_p, c_int, c_void_p, c_int, c_float, c_void_p]),
+    "rv_stage_profile": (c_int, [c_void_p, c_int]),
+    "rv_stage_profile_read": (c_int, [c_void_p, ctypes.POINTER(c_int), ctypes.POINTER(c_float)]),
     "rv_strerror": (ctypes.c_char_p, [c_int]),
 }
 

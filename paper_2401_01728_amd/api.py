@@ -113,6 +113,15 @@ class Stage:
         _check(_lib.lib().rv_stage_last_grad(self._h, _ptr(_dev_f32(out)), out.numel()))
         return out
 
+    def profile(self, on=True):
+        _check(_lib.lib().rv_stage_profile(self._h, 1 if on else 0))
+
+    def profile_read(self):
+        """(launches, mean microseconds) of the grouped weight-gradient launches bracketed so far."""
+        n, us = ctypes.c_int(0), ctypes.c_float(0.0)
+        _check(_lib.lib().rv_stage_profile_read(self._h, ctypes.byref(n), ctypes.byref(us)))
+        return n.value, us.value
+
     def _act(self, t, shape):
         assert t.is_cuda and t.dtype == self.act_dtype and t.is_contiguous() and tuple(t.shape) == tuple(shape), \
             (t.dtype, tuple(t.shape), shape)

@@ -229,7 +229,18 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
     RV_TRY(rv_attn_bwd(qkv, a, dtmp, (const float*)(sb + p.s_lse), Dbuf, dqkv, p.mb, p.S, d, p.H, st));
     wgrad(3, u, d, dqkv, 3 * d, d, 3 * d, gl + p.wqkv);                                              // dWqkv = u^T dqkv
     RV_TRY(side_begin());
-    RV_TRY(rv_gemm_wgrad_grouped(wg, 4, ws));
+    if (s->prof_on) {   // measurement aid: bracket the launch with events on its own stream
+      hipEvent_t e0 = nullptr, e1 = nullptr;
+      RV_HIP_TRY(hipEventCreate(&e0));
+      s->prof_ev.push_back(e0);
+      RV_HIP_TRY(hipEventCreate(&e1));
+      s->prof_ev.push_back(e1);
+      RV_HIP_TRY(hipEventRecord(e0, ws));
+      RV_TRY(rv_gemm_wgrad_grouped(wg, 4, ws));
+      RV_HIP_TRY(hipEventRecord(e1, ws));
+    } else {
+      RV_TRY(rv_gemm_wgrad_grouped(wg, 4, ws));
+    }
     RV_TRY(rv_colsum_bf16(dqkv, 3 * d, T, 3 * d, part_cs, ws));
     RV_TRY(rv_reduce_rows(part_cs, cs_parts, 3 * d, 3 * d, gl + p.bqkv, ws));
     RV_TRY(gemm(sh, st, dqkv, 3 * d, 0, w + p.wqkv, 3 * d, 0, T, d, 3 * d, RV_EPI_BF16, dtmp, d));       // du

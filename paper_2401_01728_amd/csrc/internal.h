@@ -97,6 +97,10 @@ struct rv_stage {
   char* work = nullptr;     // scratch shared by all calls of this stage
   size_t work_bytes = 0;
   void* impl = nullptr;     // kind-specific plan (offsets, shapes)
+  // rv_stage_profile: event pairs around every launch of the block's grouped weight-gradient
+  // product, on the stream it is launched on
+  bool prof_on = false;
+  std::vector<hipEvent_t> prof_ev;   // start, stop, start, stop, ...
 };
 
 // ---- mlp.hip -----------------------------------------------------------------------

@@ -22,6 +22,7 @@ int copy_kind(const rv_stage* s) { return s->dtype == RV_BF16 ? 1 : 2; }
 void free_all(rv_stage* s) {
   if (!s) return;
   if (s->kind == RV_MLP) rv_mlp_free(s); else rv_dec_free(s);
+  for (hipEvent_t ev : s->prof_ev) if (ev) (void)hipEventDestroy(ev);
   if (s->ev_fork) (void)hipEventDestroy(s->ev_fork);
   if (s->ev_join) (void)hipEventDestroy(s->ev_join);
   if (s->aux) (void)hipStreamDestroy(s->aux);
@@ -173,6 +174,32 @@ extern "C" rv_status rv_cluster_sync(rv_stage* const* stages, int C, int R, int 
     s->cur = dst[c];
   }
   return RV_OK;
+}
+
+extern "C" rv_status rv_stage_profile(rv_stage* s, int on) {
+  if (!s) return RV_E_INVAL;
+  s->prof_on = on != 0;
+  return RV_OK;
+}
+
+extern "C" rv_status rv_stage_profile_read(rv_stage* s, int* launches, float* mean_us) {
+  if (!s || !launches || !mean_us) return RV_E_INVAL;
+  RV_HIP_TRY(hipStreamSynchronize(s->st));
+  if (s->aux) RV_HIP_TRY(hipStreamSynchronize(s->aux));
+  if (s->wgs) RV_HIP_TRY(hipStreamSynchronize(s->wgs));
+  double sum_ms = 0.0;
+  int n = 0;
+  rv_status rc = RV_OK;
+  for (size_t i = 0; i + 1 < s->prof_ev.size(); i += 2) {
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, s->prof_ev[i], s->prof_ev[i + 1]) == hipSuccess) { sum_ms += ms; ++n; }
+    else { (void)hipGetLastError(); rc = RV_E_DEVICE; }
+  }
+  for (hipEvent_t ev : s->prof_ev) if (ev) (void)hipEventDestroy(ev);
+  s->prof_ev.clear();
+  *launches = n;
+  *mean_us = n ? (float)(sum_ms * 1e3 / n) : 0.f;
+  return rc;
 }
 
 extern "C" rv_status rv_stage_get_params(const rv_stage* s, float* flat_out, size_t n) {

@@ -21,3 +21,19 @@ def pytest_collection_modifyitems(config, items):
     for it in items:
         if "gpu" in it.keywords:
             it.add_marker(skip)
+
+
+def pytest_terminal_summary(terminalreporter):
+    """Achieved parity errors of this run against their bars (filled by util.close)."""
+    try:
+        from util import MARGINS
+    except Exception:
+        return
+    if not MARGINS:
+        return
+    tr = terminalreporter
+    tr.write_line("")
+    tr.write_line("parity margins: worst achieved error (normwise | element-wise |got-ref|/(|ref|+16 rms)) against the bar")
+    for key in sorted(MARGINS):
+        tol, e_norm, e_elem, n = MARGINS[key]
+        tr.write_line("  %-58s %9.2e | %9.2e  bar %7.1e  (%d tensors)" % (key[:58], e_norm, e_elem, tol, n))

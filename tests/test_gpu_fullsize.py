@@ -1,96 +1,107 @@
 """Parity at the benchmark shapes, in the launch configuration bench.py times.
 
-config 2 (4 blocks, d 1024, seq 512, microbatch 8): one whole stage step against the
-oracle - out, grad_in, every parameter-gradient tensor, the update.
-configs 3 and 5 (d 2048 x 8 blocks; d 1600, 25 heads x 12 blocks): the GPU runs the full
-microbatch; sequences are independent in the forward and in the input gradient, so the
-oracle computes ONE sequence and that slice of out / grad_in is compared (a full fp64 step
-would take the host tens of minutes).  Parameter gradients at these two shapes are covered
-by the reduced-shape schedules in test_gpu_decoder.py.
-config 4 (N = 1e9, C = 16, folded gradient, R in {1,2,4,8}): windows around every ring and
-chunk boundary plus random indices, regenerated on the host from the counter generator,
-bit-exact against the fp32 ring-order twin and within the 1e-6 bound of the fp64 mean.
+configs 2, 3, 5 (decoder stages at full shape): the stale schedule of Alg. 1 / Eq. 2 - tau
+warm-up forwards, then tau + 2 (config 2: 2 tau + 2) stage steps through rv_stage_step, so the
+last backwards run at the full staleness tau - against oracle/stage.py: `out` of every forward,
+`grad_in`, EVERY parameter-gradient tensor and the update of every step, element by element
+(util.close).  The oracle's block function is evaluated one sequence per process (seqpool.py).
+Averages at the configs' own sizes (C = 4 / R = 4 at 50 384 896, C = 8 / R = 4 at 402 866 176,
+C = 8 / R = 8 at 368 889 600, write-back) and config 4 (N = 1e9, C = 16, folded gradient,
+R in {1,2,4,8}): windows around every ring and chunk boundary plus random indices, regenerated
+on the host from the counter generator, bit-exact against the fp32 ring-order twin and within
+the 1e-6 bound of the fp64 mean.
 """
+import time
+
 import numpy as np
 import pytest
 import torch
 
-from oracle import average, blocks, stage as ostage
+from oracle import average, blocks
 from paper_2401_01728_amd.inputs import gen
-from util import bf16_normal, dev, host64, rel_l2
-from test_gpu_decoder import TOL, check_tensors, decoder_params_host
+from seqpool import PooledStage, SeqPool
+from util import close, dev, host64
+from test_gpu_decoder import TOL, check_tensors, check_update, decoder_params_host
 
 pytestmark = pytest.mark.gpu
 
-
-def test_config2_full_stage_step():
-    import paper_2401_01728_amd as rv
-    L, d, H, f, S, mb, tau, eta = 4, 1024, 16, 4096, 512, 8, 2, 1e-3
-    shapes = blocks.decoder_param_shapes(L, d, f)
-    w0 = decoder_params_host(2, L, d, f)
-    assert w0.size == 50384896
-    g = rv.Stage.decoder(L, d, H, f, S, mb, tau, eta); g.set_params(dev(w0))
-    o = ostage.Stage("decoder", tau, eta, w0, n_blocks=L, d=d, h=H, f=f)
-    x, x64 = bf16_normal(2, 1000, (mb, S, d))
-    dy, dy64 = bf16_normal(2, 2000, (mb, S, d), std=1e-3)
-    y = g.forward(0, x)
-    assert rel_l2(host64(y), o.forward(0, x64)) < TOL
-    dx = g.backward(0, dy)
-    dxo = o.backward(0, dy64)
-    assert rel_l2(host64(dx), dxo) < TOL
-    gg = host64(g.last_grad())
-    check_tensors(gg, o.last_grad, shapes, what="config 2")
-    w_new = host64(g.get_params())
-    assert np.all(np.abs(w_new - (w0.astype(np.float64) - np.float64(np.float32(eta)) * gg))
-                  <= 1e-6 * (np.abs(w0) + eta * np.abs(gg)))
+STAGES = {   # name: L, d, H, f, S, mb, tau, seed, number of rv_stage_step calls
+    "config2": (4, 1024, 16, 4096, 512, 8, 2, 2, 6),
+    "config3": (8, 2048, 16, 8192, 1024, 4, 3, 3, 5),
+    "config5": (12, 1600, 25, 6400, 1024, 8, 4, 5, 6),
+}
 
 
-@pytest.mark.parametrize("name,L,d,H,f,S,mb,tau", [("config3", 8, 2048, 16, 8192, 1024, 4, 3),
-                                                    ("config5", 12, 1600, 25, 6400, 1024, 8, 4)])
-def test_large_stage_one_sequence(name, L, d, H, f, S, mb, tau):
-    import paper_2401_01728_amd as rv
+def device_params(seed, L, d, f):
+    """decoder_params_host's recipe on the device (same bits, see test_inputs.py)."""
     from paper_2401_01728_amd.inputs import device
-    seed = 3 if name == "config3" else 5
     per = 4 * d * d + 2 * d * f + 9 * d + f
     w = torch.empty(L * per, dtype=torch.float32, device="cuda")
-    device.fill_normal_(w, seed, 0, 0.0, 0.02)            # same recipe as decoder_params_host, on the device
+    device.fill_normal_(w, seed, 0, 0.0, 0.02)
     for l in range(L):
         w[l * per:l * per + d] += 1.0
         o2 = l * per + 2 * d + 3 * d * d + 3 * d + d * d + d
         w[o2:o2 + d] += 1.0
-    g = rv.Stage.decoder(L, d, H, f, S, mb, tau, 1e-3); g.set_params(w)
-    x, x64 = bf16_normal(seed, 1000, (mb, S, d))
-    dy, dy64 = bf16_normal(seed, 2000, (mb, S, d), std=1e-3)
-    # the fused step needs tau microbatches in flight first; use the plain calls here and the
-    # fused call for a second microbatch so both launch paths run at this shape
-    y = g.forward(0, x)
-    y1, dx = g.step(1, x, 0, dy)
-    b = 1
-    o = ostage.Stage("decoder", 0, 1e-3, w.cpu().numpy(), n_blocks=L, d=d, h=H, f=f)
-    yo = o.forward(0, x64[b:b + 1])
-    assert rel_l2(host64(y[b:b + 1]), yo) < TOL
-    assert rel_l2(host64(y1[b:b + 1]), yo) < TOL          # forward(1) ran before the update: same weights
-    dxo = o.backward(0, dy64[b:b + 1])
-    assert rel_l2(host64(dx[b:b + 1]), dxo) < TOL
+    return w
 
 
-@pytest.mark.parametrize("R", [1, 2, 4, 8])
-def test_config4_sampled(R):
+def device_bf16(seed, stream, shape, std):
+    from paper_2401_01728_amd.inputs import device
+    t = device.fill_normal_(torch.empty(shape, dtype=torch.bfloat16, device="cuda"), seed, stream, 0.0, std)
+    return t, host64(t)
+
+
+
+@pytest.mark.parametrize("name", list(STAGES))
+def test_stale_schedule_at_full_shape(name, capsys):
+    import paper_2401_01728_amd as rv
+    L, d, H, f, S, mb, tau, seed, n_steps = STAGES[name]
+    eta = 1e-3
+    shapes = blocks.decoder_param_shapes(L, d, f)
+    w = device_params(seed, L, d, f)
+    if name == "config2":
+        assert np.array_equal(w.cpu().numpy(), decoder_params_host(seed, L, d, f))
+        assert w.numel() == 50384896
+    g = rv.Stage.decoder(L, d, H, f, S, mb, tau, eta); g.set_params(w)
+    t0 = time.time()
+    with SeqPool(L, d, H, f, S, mb) as pool:
+        o = PooledStage(pool, "decoder", tau, eta, w.cpu().numpy(), n_blocks=L, d=d, h=H, f=f)
+        del w
+        for t in range(tau + n_steps):
+            j = t - tau
+            x, x64 = device_bf16(seed, 1000 + t, (mb, S, d), 1.0)
+            if j >= 0:
+                dy, dy64 = device_bf16(seed, 2000 + j, (mb, S, d), 1e-3)
+                w_old = g.get_params().cpu().numpy()
+                y, dx = g.step(t, x, j, dy)             # forward(t) beside backward(t - tau), then the update
+            else:
+                y = g.forward(t, x)
+            close(host64(y), o.forward(t, x64), TOL, "%s out %d" % (name, t), group=name + " full shape: out")
+            if j >= 0:
+                dxo = o.backward(j, dy64)
+                assert o.last_staleness == min(j, tau)
+                close(host64(dx), dxo, TOL, "%s grad_in %d" % (name, j), group=name + " full shape: grad_in")
+                gg = g.last_grad().cpu().numpy()
+                check_tensors(gg, o.last_grad, shapes, what="%s step %d" % (name, j),
+                              group=name + " full shape: param grads")
+                check_update(g.get_params().cpu().numpy(), w_old, gg, eta)
+            with capsys.disabled():     # progress of a test that runs for minutes, past pytest's capture
+                print("%s: microbatch %d forwarded%s, %.0f s" % (
+                    name, t, "" if j < 0 else ", %d backwarded at staleness %d" % (j, o.last_staleness),
+                    time.time() - t0), flush=True)
+        assert o.last_staleness == tau and o.k == n_steps and g.in_flight == tau
+
+
+def _sampled_average(n, C, R, seed, make_replica, host_replica_at, grad_std, eta, gr, write_back):
+    """rv_cluster_average on device-generated replicas; sampled indices regenerated on the host."""
     import paper_2401_01728_amd as rv
     from paper_2401_01728_amd.inputs import device
-    n, C, eta, seed, gr = 1_000_000_000, 16, 1e-3, 4, 0
-    if torch.cuda.get_device_properties(0).total_memory < 90e9:
-        pytest.skip("needs 72 GB of device memory")
-    shared = device.fill_normal_(torch.empty(n, dtype=torch.float32, device="cuda"), seed, 0)
-    reps = []
-    for c in range(C):
-        r = device.fill_normal_(torch.empty(n, dtype=torch.float32, device="cuda"), seed, 1 + c)
-        r += shared
-        reps.append(r)
-    del shared
-    grad = device.fill_normal_(torch.empty(n, dtype=torch.float32, device="cuda"), seed, 99, 0.0, 1e-3)
+    reps = [make_replica(c) for c in range(C)]
+    grad = None
+    if grad_std:
+        grad = device.fill_normal_(torch.empty(n, dtype=torch.float32, device="cuda"), seed, 99, 0.0, grad_std)
     out = torch.empty(n, dtype=torch.float32, device="cuda")
-    rv.cluster_average(reps, R, mean_out=out, grad=grad, grad_replica=gr, eta=eta)
+    rv.cluster_average(reps, R, mean_out=out, write_back=write_back, grad=grad, grad_replica=gr, eta=eta)
     torch.cuda.synchronize()
     # sample: +-40 elements around every chunk boundary, the two ends, 1e6 random indices
     bounds = average.ring_partition(n, R, C)
@@ -100,18 +111,21 @@ def test_config4_sampled(R):
             idx.append(np.arange(max(e - 40, 0), min(e + 40, n)))
     idx.append(np.random.default_rng(R).integers(0, n, size=1_000_000))
     idx = np.unique(np.concatenate(idx)).astype(np.uint64)
-    o = gen.normal_f32_at(seed, 0, idx)
-    xs = [(o + gen.normal_f32_at(seed, 1 + c, idx)).astype(np.float32) for c in range(C)]
-    gh = gen.normal_f32_at(seed, 99, idx, 0.0, 1e-3)
-    got = out[torch.from_numpy(idx.astype(np.int64)).cuda()].cpu().numpy()
+    xs = [host_replica_at(c, idx) for c in range(C)]
+    tidx = torch.from_numpy(idx.astype(np.int64)).cuda()
+    got = out[tidx].cpu().numpy()
     # owning chunk of every sampled index -> rotation of the ring-order sum
     j_of = np.empty(idx.size, dtype=np.int64)
     for rb in bounds:
         for j in range(C):
             m = (idx >= rb[j]) & (idx < rb[j + 1])
             j_of[m] = j
-    step = gh * np.float32(eta)
-    xs[gr] = xs[gr] - step
+    if grad is not None:
+        gh = gen.normal_f32_at(seed, 99, idx, 0.0, grad_std)
+        step = gh * np.float32(eta)
+        xs[gr] = xs[gr] - step
+    else:
+        gh = step = np.zeros(idx.size, dtype=np.float32)
     X = np.stack(xs)                                      # [C, m] fp32
     acc = X[j_of % C, np.arange(idx.size)].copy()
     for s in range(1, C):
@@ -121,6 +135,56 @@ def test_config4_sampled(R):
     ref = X.astype(np.float64).mean(axis=0)               # xs[gr] already holds the folded step (fp32 inputs)
     bound = 1e-6 * (np.abs(X).astype(np.float64).mean(axis=0) + eta * np.abs(gh) / C)
     assert np.all(np.abs(got.astype(np.float64) - ref) <= bound + 1e-6 * np.abs(step) / C)
+    if write_back:                                        # the state a cycle ends in: every replica holds the mean
+        for r in reps:
+            assert np.array_equal(r[tidx].cpu().numpy().view(np.uint32), got.view(np.uint32))
+
+
+@pytest.mark.parametrize("R", [1, 2, 4, 8])
+def test_config4_sampled(R):
+    from paper_2401_01728_amd.inputs import device
+    n, C, seed = 1_000_000_000, 16, 4
+    if torch.cuda.get_device_properties(0).total_memory < 90e9:
+        pytest.skip("needs 72 GB of device memory")
+    shared = device.fill_normal_(torch.empty(n, dtype=torch.float32, device="cuda"), seed, 0)
+
+    def make(c):
+        r = device.fill_normal_(torch.empty(n, dtype=torch.float32, device="cuda"), seed, 1 + c)
+        r += shared
+        return r
+    o_at = {}
+
+    def host(c, idx):
+        if "o" not in o_at:
+            o_at["o"] = gen.normal_f32_at(seed, 0, idx)
+        return (o_at["o"] + gen.normal_f32_at(seed, 1 + c, idx)).astype(np.float32)
+    _sampled_average(n, C, R, seed, make, host, 1e-3, 1e-3, 0, False)
+
+
+@pytest.mark.parametrize("name,C,R", [("config2", 4, 4), ("config3", 8, 4), ("config5", 8, 8)])
+def test_average_at_the_stage_sizes(name, C, R):
+    """C replicas of the stage's parameter vector: the stage's own initial parameters plus a
+    per-replica N(0, 0.002) perturbation; plain mean (no folded step), written back to all."""
+    from paper_2401_01728_amd.inputs import device
+    L, d, H, f, S, mb, tau, seed, _ = STAGES[name]
+    per = 4 * d * d + 2 * d * f + 9 * d + f
+    n = L * per
+    assert n == {"config2": 50384896, "config3": 402866176, "config5": 368889600}[name]
+    base = device_params(seed, L, d, f)
+
+    def make(c):
+        r = device.fill_normal_(torch.empty(n, dtype=torch.float32, device="cuda"), seed, 100 + c, 0.0, 0.002)
+        r += base
+        return r
+
+    def host(c, idx):
+        w = gen.normal_f32_at(seed, 0, idx, 0.0, 0.02)
+        p = (idx % np.uint64(per)).astype(np.int64)
+        o2 = 2 * d + 3 * d * d + 3 * d + d * d + d
+        gamma = (p < d) | ((p >= o2) & (p < o2 + d))
+        w[gamma] += np.float32(1.0)
+        return (gen.normal_f32_at(seed, 100 + c, idx, 0.0, 0.002) + w).astype(np.float32)
+    _sampled_average(n, C, R, seed, make, host, 0.0, 0.0, 0, True)
 
 
 @pytest.mark.parametrize("name,L,d,H,f,S,mb,tau", [("config2", 4, 1024, 16, 4096, 512, 8, 2),

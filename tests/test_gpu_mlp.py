@@ -10,7 +10,7 @@ import torch
 
 from oracle import blocks, stage as ostage
 from paper_2401_01728_amd.inputs import gen
-from util import dev, host64, rel_l2
+from util import close, dev, host64, rel_l2
 
 pytestmark = pytest.mark.gpu
 
@@ -45,16 +45,16 @@ def test_two_stage_chain_config1():
     for t in range(n_mb + 1):
         if t < n_mb:
             h_g = g_st[0].forward(t, dev(xs[t])); h_o = o_st[0].forward(t, xs[t])
-            assert rel_l2(host64(h_g), h_o) < 1e-5
+            close(host64(h_g), h_o, 1e-5, "t", group="MLP stage, bar 1e-5")
             y_g = g_st[1].forward(t, h_g); y_o = o_st[1].forward(t, h_o)
-            assert rel_l2(host64(y_g), y_o) < 1e-5
+            close(host64(y_g), y_o, 1e-5, "t", group="MLP stage, bar 1e-5")
             dy_g = (2.0 / y_g.numel()) * (y_g - dev(ts[t]))          # harness: MSE gradient
             dy_o = 2.0 * (y_o - ts[t]) / y_o.size
             w_old = host64(g_st[1].get_params())
             dh_g = g_st[1].backward(t, dy_g.contiguous()); dh_o = o_st[1].backward(t, dy_o)
-            assert rel_l2(host64(dh_g), dh_o) < 2e-5
+            close(host64(dh_g), dh_o, 2e-5, "t", group="MLP stage, bar 2e-5")
             gg = host64(g_st[1].last_grad())
-            assert rel_l2(gg, o_st[1].last_grad) < 2e-5
+            close(gg, o_st[1].last_grad, 2e-5, "t", group="MLP stage, bar 2e-5")
             w_new = host64(g_st[1].get_params())
             assert np.all(np.abs(w_new - (w_old - np.float64(np.float32(eta)) * gg)) <= 1e-6 * (np.abs(w_old) + eta * np.abs(gg)))
             pending[t] = (dh_g, dh_o)
@@ -63,10 +63,10 @@ def test_two_stage_chain_config1():
             dh_g, dh_o = pending.pop(j)
             dx_g = g_st[0].backward(j, dh_g); dx_o = o_st[0].backward(j, dh_o)
             assert o_st[0].last_staleness == min(j, 1)
-            assert rel_l2(host64(dx_g), dx_o) < 5e-5
-            assert rel_l2(host64(g_st[0].last_grad()), o_st[0].last_grad) < 5e-5
+            close(host64(dx_g), dx_o, 5e-5, "t", group="MLP stage, bar 5e-5")
+            close(host64(g_st[0].last_grad()), o_st[0].last_grad, 5e-5, "t", group="MLP stage, bar 5e-5")
     for s in range(2):
-        assert rel_l2(host64(g_st[s].get_params()), o_st[s].w) < 1e-6
+        close(host64(g_st[s].get_params()), o_st[s].w, 1e-6, "t", group="MLP stage, bar 1e-6")
         assert g_st[s].in_flight == 0
 
 
@@ -82,14 +82,14 @@ def test_general_shapes_and_fifo_schedule(dims, mb, tau):
     dys = [gen.normal_f32(5, 50 + t, mb * dims[-1]).reshape(mb, dims[-1]) for t in range(n)]
     for t in range(n + tau):
         if t < n:
-            assert rel_l2(host64(g.forward(t, dev(xs[t]))), o.forward(t, xs[t])) < 1e-5
+            close(host64(g.forward(t, dev(xs[t]))), o.forward(t, xs[t]), 1e-5, "t", group="MLP stage, bar 1e-5")
             assert g.in_flight == len(o.live)
         j = t - tau
         if j >= 0:
             dx = g.backward(j, dev(dys[j])); dxo = o.backward(j, dys[j])
-            assert rel_l2(host64(dx), dxo) < 1e-5
-            assert rel_l2(host64(g.last_grad()), o.last_grad) < 1e-5
-    assert rel_l2(host64(g.get_params()), o.w) < 1e-6
+            close(host64(dx), dxo, 1e-5, "t", group="MLP stage, bar 1e-5")
+            close(host64(g.last_grad()), o.last_grad, 1e-5, "t", group="MLP stage, bar 1e-5")
+    close(host64(g.get_params()), o.w, 1e-6, "t", group="MLP stage, bar 1e-6")
 
 
 def test_out_of_order_backward_keeps_versions_apart():
@@ -104,11 +104,11 @@ def test_out_of_order_backward_keeps_versions_apart():
     order = [("f", 0), ("f", 1), ("b", 1), ("f", 2), ("b", 2), ("f", 3), ("b", 3), ("f", 4), ("b", 0), ("b", 4)]
     for op, t in order:
         if op == "f":
-            assert rel_l2(host64(g.forward(t, dev(x(t)))), o.forward(t, x(t))) < 1e-5
+            close(host64(g.forward(t, dev(x(t)))), o.forward(t, x(t)), 1e-5, "t", group="MLP stage, bar 1e-5")
         else:
-            assert rel_l2(host64(g.backward(t, dev(dy(t)))), o.backward(t, dy(t))) < 1e-5
-            assert rel_l2(host64(g.last_grad()), o.last_grad) < 1e-5
-    assert rel_l2(host64(g.get_params()), o.w) < 1e-6
+            close(host64(g.backward(t, dev(dy(t)))), o.backward(t, dy(t)), 1e-5, "t", group="MLP stage, bar 1e-5")
+            close(host64(g.last_grad()), o.last_grad, 1e-5, "t", group="MLP stage, bar 1e-5")
+    close(host64(g.get_params()), o.w, 1e-6, "t", group="MLP stage, bar 1e-6")
 
 
 def test_error_paths_leave_state_unchanged():
@@ -145,12 +145,12 @@ def test_stage_with_momentum_and_weight_decay():
     for t in range(n + tau):
         if t < n:
             x = gen.normal_f32(8, 10 + t, mb * dims[0]).reshape(mb, dims[0])
-            assert rel_l2(host64(g.forward(t, dev(x))), o.forward(t, x)) < 1e-5
+            close(host64(g.forward(t, dev(x))), o.forward(t, x), 1e-5, "t", group="MLP stage, bar 1e-5")
         j = t - tau
         if j >= 0:
             dy = gen.normal_f32(8, 50 + j, mb * dims[-1]).reshape(mb, dims[-1])
-            assert rel_l2(host64(g.backward(j, dev(dy))), o.backward(j, dy)) < 1e-5
-    assert rel_l2(host64(g.get_params()) - w0, o.w - w0) < 1e-4
+            close(host64(g.backward(j, dev(dy))), o.backward(j, dy), 1e-5, "t", group="MLP stage, bar 1e-5")
+    close(host64(g.get_params()) - w0, o.w - w0, 1e-4, "t", group="MLP stage, bar 1e-4")
     with pytest.raises(rv.RvError):
         g.set_optimizer(-1.0, 0.0)
 
@@ -170,15 +170,15 @@ def test_stage_with_gradient_accumulation(A, momentum):
     for t in range(n + tau):
         if t < n:
             x = gen.normal_f32(8, 10 + t, mb * dims[0]).reshape(mb, dims[0])
-            assert rel_l2(host64(g.forward(t, dev(x))), o.forward(t, x)) < 1e-5
+            close(host64(g.forward(t, dev(x))), o.forward(t, x), 1e-5, "t", group="MLP stage, bar 1e-5")
         j = t - tau
         if j >= 0:
             dy = gen.normal_f32(8, 50 + j, mb * dims[-1]).reshape(mb, dims[-1])
             before = g.get_params().clone()
-            assert rel_l2(host64(g.backward(j, dev(dy))), o.backward(j, dy)) < 1e-5
-            assert rel_l2(host64(g.last_grad()), o.last_grad) < 1e-5
+            close(host64(g.backward(j, dev(dy))), o.backward(j, dy), 1e-5, "t", group="MLP stage, bar 1e-5")
+            close(host64(g.last_grad()), o.last_grad, 1e-5, "t", group="MLP stage, bar 1e-5")
             moved = not torch.equal(before, g.get_params())
             assert moved == ((j + 1) % A == 0)
-    assert rel_l2(host64(g.get_params()) - w0, o.w - w0) < 1e-4
+    close(host64(g.get_params()) - w0, o.w - w0, 1e-4, "t", group="MLP stage, bar 1e-4")
     with pytest.raises(rv.RvError):
         g.set_accumulation(0)

@@ -200,3 +200,28 @@ def test_accumulation_with_staleness_against_separate_loop():
                 w = w - eta * acc; acc = np.zeros_like(w); cnt = 0; updates += 1
     assert np.allclose(st.w, w, rtol=0, atol=1e-15)
     assert max(stal) == 1 and min(stal) == 0               # staleness is counted in updates
+
+
+def test_sequence_pool_equals_the_stacked_microbatch():
+    """The full-size GPU parity tests evaluate the oracle one sequence per process (seqpool.py):
+    a stale schedule through that harness must give what oracle.stage.Stage gives on the whole
+    microbatch (sequences are independent; the parameter gradient is their sum)."""
+    from seqpool import PooledStage, SeqPool
+    L, d, h, f, S, mb, tau, eta = 2, 16, 2, 24, 6, 3, 2, 0.05
+    rng = np.random.default_rng(3)
+    P = blocks.num_params(blocks.decoder_param_shapes(L, d, f))
+    w0 = rng.normal(size=P) * 0.3
+    xs = [rng.normal(size=(mb, S, d)) for _ in range(5)]
+    dys = [rng.normal(size=(mb, S, d)) for _ in range(5)]
+    with SeqPool(L, d, h, f, S, mb, workers=2) as pool:        # 2 workers, 3 sequences: one worker sums two
+        a = stage.Stage("decoder", tau, eta, w0, n_blocks=L, d=d, h=h, f=f)
+        b = PooledStage(pool, "decoder", tau, eta, w0, n_blocks=L, d=d, h=h, f=f)
+        for t in range(5 + tau):
+            if t < 5:
+                assert np.allclose(a.forward(t, xs[t]), b.forward(t, xs[t]), rtol=0, atol=1e-13)
+            j = t - tau
+            if j >= 0:
+                assert np.allclose(a.backward(j, dys[j]), b.backward(j, dys[j]), rtol=0, atol=1e-13)
+                assert np.allclose(a.last_grad, b.last_grad, rtol=1e-12, atol=1e-13)
+                assert a.last_staleness == b.last_staleness == min(j, tau)
+        assert np.allclose(a.w, b.w, rtol=0, atol=1e-13)

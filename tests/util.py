@@ -34,3 +34,41 @@ def rel_l2(a, b):
 def max_rel(a, b):
     a = np.asarray(a, dtype=np.float64).ravel(); b = np.asarray(b, dtype=np.float64).ravel()
     return float(np.abs(a - b).max() / max(np.abs(b).max(), 1e-300))
+
+
+# ---- comparison with recorded margins -------------------------------------------------------
+# Every parity check goes through close(): the normwise relative error against `tol`, and an
+# element-wise bound |got - ref| <= tol * (|ref| + SPREAD * rms(ref)) that a single wrong element
+# cannot hide behind the norm of the rest.  Why SPREAD = 16: rounding errors of a tensor of up to
+# 1e8 elements whose normwise error is e have a largest member of about 6 e rms when they are
+# evenly spread, and more where they are not: in the q and k thirds of a Wqkv gradient (the
+# attention backward rounds dS to bf16 before its two products) the error kurtosis is 10-13 and
+# the largest error measured at the benchmark shapes is 0.16 rms, half of what the bar allows at
+# tol = 2e-2.  One element that is simply wrong (off by the tensor's own scale, 1 rms) is still
+# three times outside it.
+# The achieved errors are kept and printed at the end of the run (conftest.py), so the margin to
+# the bar is on record.
+MARGINS = {}
+SPREAD = 16.0
+
+
+def errors(got, ref):
+    """(normwise relative error, max over elements of |got-ref| / (|ref| + SPREAD * rms(ref)))."""
+    got = np.asarray(got, dtype=np.float64).ravel(); ref = np.asarray(ref, dtype=np.float64).ravel()
+    diff = got - ref
+    nrm = float(np.linalg.norm(ref))
+    rms = nrm / np.sqrt(max(ref.size, 1))
+    if nrm == 0.0:
+        worst = float(np.abs(diff).max()) if diff.size else 0.0
+        return worst, worst
+    return float(np.linalg.norm(diff) / nrm), float((np.abs(diff) / (np.abs(ref) + SPREAD * rms)).max())
+
+
+def close(got, ref, tol, what, group=None):
+    e_norm, e_elem = errors(got, ref)
+    key = group or what
+    w = MARGINS.setdefault(key, [tol, 0.0, 0.0, 0])
+    w[1] = max(w[1], e_norm); w[2] = max(w[2], e_elem); w[3] += 1
+    assert np.isfinite(e_norm) and e_norm < tol, (what, "normwise", e_norm, tol)
+    assert e_elem <= tol, (what, "element-wise", e_elem, tol)
+    return e_norm, e_elem
