@@ -19,8 +19,11 @@
  *   - Every call validates its arguments on the host, enqueues its work on the
  *     stage's (or the given) hipStream_t and returns without synchronising.
  *     A caller buffer may be reused once the stream has passed the call.
- *   - Errors are returned, never thrown; after a non-OK return the stage state
- *     is unchanged.
+ *   - Errors are returned, never thrown.  Arguments and stage state are checked before
+ *     anything is enqueued: after RV_E_INVAL, RV_E_STASH_FULL, RV_E_UNKNOWN_MB, RV_E_DUP_MB
+ *     or RV_E_NOMEM the stage state is unchanged.  RV_E_DEVICE means a HIP call failed,
+ *     possibly with part of the call's work already enqueued: the stage (for
+ *     rv_cluster_sync: every stage passed) is then fit only for rv_stage_destroy.
  *
  * Canonical flat parameter order (what set/get_params, last_grad and the
  * average see), layers in forward order, every matrix row-major [in, out]:
@@ -69,7 +72,8 @@ typedef enum { RV_F32 = 0, RV_BF16 = 1 } rv_dtype;
  *   tau             : largest number of updates that may happen between a
  *                     microbatch's forward and its backward (the staleness bound
  *                     of Eq. 2); the stage keeps tau+1 activation-stash slots and
- *                     tau+1 weight versions.
+ *                     tau+2 weight versions (tau+1 in use by microbatches in flight, one
+ *                     being written by the update).
  *   eta             : learning rate of Eq. 2.
  *   stream          : hipStream_t (borrowed); NULL = the default stream.
  */
@@ -85,7 +89,7 @@ typedef struct {
   void* stream;
 } rv_stage_desc;
 
-/* Allocates master parameters (zero), gradient buffer, tau+1 weight versions and
+/* Allocates master parameters (zero), gradient buffer, tau+2 weight versions and
  * tau+1 stash slots on the current device.  RV_E_INVAL / RV_E_NOMEM / RV_E_DEVICE. */
 rv_status rv_stage_create(const rv_stage_desc* desc, rv_stage** out);
 rv_status rv_stage_destroy(rv_stage* s);
@@ -101,8 +105,15 @@ int rv_stage_in_flight(const rv_stage* s);
 rv_status rv_stage_set_params(rv_stage* s, const float* flat, size_t n);
 /* Copy the fp32 master vector into flat_out (device [n], n == P). */
 rv_status rv_stage_get_params(const rv_stage* s, float* flat_out, size_t n);
-/* Copy the parameter gradient computed by the most recent backward (device [n]). */
+/* Copy the parameter gradient computed by the most recent backward (device [n]).  A decoder
+ * stage taking the plain step of Eq. 2 applies it inside the kernels that produce the gradient
+ * and keeps no copy of it unless rv_stage_keep_grad was switched on: RV_E_INVAL then, and
+ * before the first backward. */
 rv_status rv_stage_last_grad(const rv_stage* s, float* flat_out, size_t n);
+/* on != 0: backward calls also store the parameter gradient (4 more bytes written per
+ * parameter), for rv_stage_last_grad.  Off by default.  MLP stages and the momentum /
+ * accumulation / deferred-update variants always have it. */
+rv_status rv_stage_keep_grad(rv_stage* s, int on);
 
 /*
  * Optional: the optimiser of the paper's single-cluster experiments (section 4.1, SGD

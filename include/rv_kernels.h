@@ -31,8 +31,9 @@ enum {
  * and its gradient, paper Alg. 1 / Eq. 2).
  *   a_kmajor = 0: A[m*lda + k];  1: A[k*lda + m].   b_kmajor = 0: B[n*ldb + k];  1: B[k*ldb + n].
  *   Supported (a_kmajor, b_kmajor, epilogue): (0,1,{1,2,3,6}), (0,0,{0,4}), (1,1,{5}).
- *   K % 64 == 0; M, N, lda, ldb % 8 == 0; ldo, ldr % 4 == 0.  tile: 0 = automatic; 128, 192 (128x256), 256: register-staged tiles; 2128, 2192, 2256, 5256 (256x256, eight waves): the same
- *   tiles fed by the direct-to-LDS ring.
+ *   K % 64 == 0; M, N, lda, ldb % 8 == 0; ldo % 8 == 0 for bf16 outputs and % 4 for fp32 ones;
+ *   ldr % 4 == 0.  tile: 0 = automatic; 2128 (128x128), 2192 (128x256), 2256 (256x256, four
+ *   waves), 5256 (256x256, eight waves) force a tile.
  */
 rv_status rv_k_gemm_bf16(const void* A, int64_t lda, int a_kmajor, const void* B, int64_t ldb,
                          int b_kmajor, int M, int N, int K, int epilogue, void* out, int64_t ldo,

@@ -30,6 +30,7 @@ SYMBOLS = {
     "rv_cluster_sync": (c_int, [c_void_p, c_int, c_int, c_int]),
     "rv_stage_get_params": (c_int, [c_void_p, c_void_p, c_size_t]),
     "rv_stage_last_grad": (c_int, [c_void_p, c_void_p, c_size_t]),
+    "rv_stage_keep_grad": (c_int, [c_void_p, c_int]),
     "rv_stage_forward": (c_int, [c_void_p, c_int64, c_void_p, c_void_p]),
     "rv_stage_backward": (c_int, [c_void_p, c_int64, c_void_p, c_void_p]),
     "rv_stage_step": (c_int, [c_void_p, c_int64, c_void_p, c_void_p, c_int64, c_void_p, c_void_p]),

@@ -67,8 +67,12 @@ class Stage:
         return cls(RV_MLP, dims, len(dims) - 1, microbatch, tau, eta, stream=stream)
 
     @classmethod
-    def decoder(cls, n_blocks, d_model, n_heads, d_ffn, seq, microbatch, tau, eta, ln_eps=1e-5, stream=None):
-        return cls(RV_DECODER, [d_model, n_heads, d_ffn, seq], n_blocks, microbatch, tau, eta, ln_eps, stream)
+    def decoder(cls, n_blocks, d_model, n_heads, d_ffn, seq, microbatch, tau, eta, ln_eps=1e-5, stream=None,
+                keep_grad=False):
+        st = cls(RV_DECODER, [d_model, n_heads, d_ffn, seq], n_blocks, microbatch, tau, eta, ln_eps, stream)
+        if keep_grad:
+            st.keep_grad(True)
+        return st
 
     def close(self):
         if self._h is not None:
@@ -97,6 +101,9 @@ class Stage:
 
     def set_accumulation(self, microbatches):
         _check(_lib.lib().rv_stage_set_accumulation(self._h, int(microbatches)))
+
+    def keep_grad(self, on=True):
+        _check(_lib.lib().rv_stage_keep_grad(self._h, 1 if on else 0))
 
     def defer_update(self, on=True):
         _check(_lib.lib().rv_stage_defer_update(self._h, 1 if on else 0))

@@ -157,6 +157,19 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
   float* Dbuf = (float*)(s->work + p.w_D);
   float* part_cs = (float*)(s->work + p.w_part_cs);
   const int ln_parts = rv_ln_bwd_parts(T), cs_parts = rv_colsum_parts(T);
+  // fused update (plain Eq. 2): every kernel that completes a parameter gradient applies it at once
+  // to the fp32 master and writes the bf16 rounding into the new weight version `vdst`
+  uint16_t* vdst = s->fused ? (uint16_t*)s->ver[s->upd_dst] : nullptr;
+  rv_reduce_update ru;
+  ru.eta = s->eta; ru.store = s->keep_grad;
+  auto upd = [&](float* const* dst, int n) -> const rv_reduce_update* {
+    if (!s->fused) return nullptr;
+    for (int k = 0; k < n; ++k) {
+      const size_t off = (size_t)(dst[k] - s->grad);
+      ru.w[k] = s->master + off; ru.ver[k] = vdst + off;
+    }
+    return &ru;
+  };
 
   // Everything that only feeds the parameter gradient - the four weight-gradient products of a
   // block, the reductions behind the bias and LayerNorm gradients, the block's delayed update -
@@ -179,7 +192,8 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
     float* gl = s->grad + (size_t)(p.L - 1) * p.per_block;
     RV_TRY(side_begin());
     RV_TRY(rv_colsum_bf16(dres16, d, T, d, part_cs, ws));
-    RV_TRY(rv_reduce_rows(part_cs, cs_parts, d, d, gl + p.b2, ws));
+    float* out = gl + p.b2;
+    RV_TRY(rv_reduce_rows(part_cs, cs_parts, d, d, out, ws, upd(&out, 1)));
   }
   for (int l = p.L - 1; l >= 0; --l) {
     const int par = l & 1;
@@ -206,6 +220,11 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
     auto wgrad = [&](int k, const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb, int M, int N, float* out) {
       wg[k].A = A; wg[k].lda = lda; wg[k].a_kmajor = 1; wg[k].B = B; wg[k].ldb = ldb; wg[k].b_kmajor = 1;
       wg[k].M = M; wg[k].N = N; wg[k].K = T; wg[k].epi = RV_EPI_F32; wg[k].out = out; wg[k].ldo = N;
+      if (s->fused) {   // Eq. 2 in the product's epilogue: master and new weight version at the same offset
+        const size_t off = (size_t)(out - s->grad);
+        wg[k].upd_w = s->master + off; wg[k].upd_ver = vdst + off; wg[k].upd_eta = s->eta;
+        wg[k].store_out = s->keep_grad;
+      }
     };
     // feed-forward half
     wgrad(0, g, f, dres16, d, f, d, gl + p.w2);                                                      // dW2 = g^T dy
@@ -213,7 +232,10 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
     wgrad(1, v2, d, dz, f, d, f, gl + p.w1);                                                         // dW1 = v2^T dz
     RV_TRY(side_begin());
     RV_TRY(rv_colsum_bf16(dz, f, T, f, part_cs, ws));
-    RV_TRY(rv_reduce_rows(part_cs, cs_parts, f, f, gl + p.b1, ws));
+    {
+      float* out = gl + p.b1;
+      RV_TRY(rv_reduce_rows(part_cs, cs_parts, f, f, out, ws, upd(&out, 1)));
+    }
     RV_TRY(gemm(sh, st, dz, f, 0, w + p.w1, f, 0, T, d, f, RV_EPI_BF16, dtmp, d));                       // dv2 = dz W1^T
     RV_TRY(rv_ln_bwd(dtmp, x1, (const float*)(sb + p.s_m2), (const float*)(sb + p.s_r2), w + p.ln2g, dres, dres,
                      dx1_16, part2, T, d, st));
@@ -221,7 +243,7 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
       const float* src[3] = {part2, part2 + d, part2 + 2 * d};
       float* dst[3] = {gl + p.ln2g, gl + p.ln2b, gl + p.bo};                                         // dbo = sum dx1
       RV_TRY(side_begin());
-      RV_TRY(rv_reduce_rows_multi(src, dst, 3, ln_parts, 3 * (int64_t)d, d, ws));
+      RV_TRY(rv_reduce_rows_multi(src, dst, 3, ln_parts, 3 * (int64_t)d, d, ws, upd(dst, 3)));
     }
     // attention half
     wgrad(2, a, d, dx1_16, d, d, d, gl + p.wo);                                                      // dWo = a^T dx1
@@ -242,7 +264,10 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
       RV_TRY(rv_gemm_wgrad_grouped(wg, 4, ws));
     }
     RV_TRY(rv_colsum_bf16(dqkv, 3 * d, T, 3 * d, part_cs, ws));
-    RV_TRY(rv_reduce_rows(part_cs, cs_parts, 3 * d, 3 * d, gl + p.bqkv, ws));
+    {
+      float* out = gl + p.bqkv;
+      RV_TRY(rv_reduce_rows(part_cs, cs_parts, 3 * d, 3 * d, out, ws, upd(&out, 1)));
+    }
     RV_TRY(gemm(sh, st, dqkv, 3 * d, 0, w + p.wqkv, 3 * d, 0, T, d, 3 * d, RV_EPI_BF16, dtmp, d));       // du
     uint16_t* dx16 = l == 0 ? (uint16_t*)grad_in : dy_below;
     RV_TRY(rv_ln_bwd(dtmp, x, (const float*)(sb + p.s_m1), (const float*)(sb + p.s_r1), w + p.ln1g, dres, dres, dx16,
@@ -252,11 +277,12 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
       const float* src[3] = {part1, part1 + d, part1 + 2 * d};
       float* dst[3] = {gl + p.ln1g, gl + p.ln1b, l > 0 ? s->grad + (size_t)(l - 1) * p.per_block + p.b2 : nullptr};
       RV_TRY(side_begin());
-      RV_TRY(rv_reduce_rows_multi(src, dst, l > 0 ? 3 : 2, ln_parts, 3 * (int64_t)d, d, ws));
+      RV_TRY(rv_reduce_rows_multi(src, dst, l > 0 ? 3 : 2, ln_parts, 3 * (int64_t)d, d, ws, upd(dst, l > 0 ? 3 : 2)));
     }
     // every gradient of block l is complete behind this point of `ws` (its b2 gradient came
-    // from the block above): the delayed update of the block follows at once
-    RV_TRY(rv_stage_update_range(s, (size_t)l * p.per_block, p.per_block, ws));
+    // from the block above); unless the epilogues above have applied it already, the delayed
+    // update of the block follows at once
+    if (!s->fused) RV_TRY(rv_stage_update_range(s, (size_t)l * p.per_block, p.per_block, ws));
     RV_HIP_TRY(hipEventRecord(s->ev_wg_done[par], ws));
     dres16 = dy_below;               // dy of the block below
   }

@@ -9,15 +9,14 @@
 //   dX       dx = dy W^T   : A = dy k-contiguous, B = W  k-contiguous (its rows are the n's)
 //   dW       dW = x^T dy   : A = x  k-major,      B = dy k-major      (contraction over tokens)
 //
-// Tiling: a workgroup of 256 lanes (2x2 waves) owns a BM x BN tile and walks K in steps
-// of BK (64 or 32).  Tiles are staged global -> registers -> LDS, double buffered, one barrier per
-// step.  A wave owns (BM/2) x (BN/2) as 32x32 MFMA tiles (v_mfma_f32_32x32x16_bf16).
-//   k-contiguous operands sit in LDS as [row][BK k], read as one
-//   16-byte fragment per lane (pitch BK*2+16 bytes);
-//   k-major operands sit as [64 k][cols] with pitch cols*2+64 bytes and are read with the
-//   LDS transpose read (ds_read_b64_tr_b16), which hands each lane four consecutive k of
-//   one column: no register transposes, no transposed copies of activations in HBM.
-// Both pitches make the reads bank-conflict free.
+// Tiling: a workgroup of 4 or 8 waves owns a BM x BN tile and walks K in steps of BK (64 or
+// 32); a wave owns a block of 32x32 MFMA tiles (v_mfma_f32_32x32x16_bf16).  Operand tiles go
+// global -> LDS directly (global_load_lds_dwordx4) through a ring of NS stages, unpadded, bank
+// conflicts removed by an XOR swizzle (see "direct-to-LDS pipeline" below);
+//   k-contiguous operands sit in LDS as [row][BK k], read as one 16-byte fragment per lane;
+//   k-major operands sit as [BK k][cols] and are read with the LDS transpose read
+//   (ds_read_b64_tr_b16), which hands each lane four consecutive k of one column: no register
+//   transposes, no transposed copies of activations in HBM.
 // The MFMA is issued with the B fragment as its first operand, so a lane ends up with
 // four CONSECUTIVE n of one row m: epilogues store 8 (bf16) or 16 (fp32) bytes per lane.
 #include "internal.h"
@@ -31,15 +30,6 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-
-constexpr int kThreads = 256;
-
-// LDS pitches (bytes).  k-contiguous tile: [row][BK k] + 16; k-major tile: [BK k][cols] + 64.
-__host__ __device__ constexpr int pitch_kc(int bk) { return bk * 2 + 16; }
-__host__ __device__ constexpr int pitch_km(int cols) { return cols * 2 + 64; }
-__host__ __device__ constexpr int tile_bytes(bool km, int rows, int bk) {
-  return km ? bk * pitch_km(rows) : rows * pitch_kc(bk);
-}
 
 // GELU(z) = z * Phi(z) and its derivative Phi(z) + z * phi(z).  The upper tail of the normal
 // distribution, q = 1 - Phi(|z|) = erfc(|z|/sqrt 2)/2, comes from the three-term
@@ -69,99 +59,23 @@ __device__ __forceinline__ float dgelu_f(float z) {
   return __fmaf_rn(z * 0.3989422804014327f, e, cdf);
 }
 
-// ---- global -> registers ---------------------------------------------------------------
-// A lane moves N 16-byte chunks of a tile per k-step.  Their element offsets (row clamped to
-// the matrix so ragged tiles read valid memory) are computed once; a k-step only adds k0.
-template <bool KM, int ROWS, int BK>
-struct Stage {
-  static constexpr int N = ROWS * BK / 8 / kThreads;
-  u32x4 v[N];
-  int off[N];
-};
-
-// rows: extent of the non-contraction dimension (M or N) of this operand, r0: tile origin
-template <bool KM, int ROWS, int BK>
-__device__ __forceinline__ void init_tile(Stage<KM, ROWS, BK>& s, int64_t ld, int r0, int rows) {
-  const int t = threadIdx.x;
-#pragma unroll
-  for (int i = 0; i < Stage<KM, ROWS, BK>::N; ++i) {
-    const int idx = t + kThreads * i;
-    if (!KM) {
-      constexpr int CPR = BK / 8;
-      int row = r0 + idx / CPR, c = idx % CPR;
-      row = row < rows ? row : rows - 1;
-      s.off[i] = row * (int)ld + c * 8;
-    } else {
-      constexpr int CPR = ROWS / 8;
-      int kr = idx / CPR, c = idx % CPR;
-      int col = r0 + c * 8;
-      col = col < rows ? col : rows - 8;
-      s.off[i] = kr * (int)ld + col;
-    }
-  }
-}
-
-template <bool KM, int ROWS, int BK>
-__device__ __forceinline__ void load_tile(Stage<KM, ROWS, BK>& s, const uint16_t* __restrict__ g,
-                                          int64_t ld, int k0) {
-  const uint16_t* base = KM ? g + (int64_t)k0 * ld : g + k0;
-#pragma unroll
-  for (int i = 0; i < Stage<KM, ROWS, BK>::N; ++i)
-    s.v[i] = *reinterpret_cast<const u32x4*>(base + s.off[i]);
-}
-
-template <bool KM, int ROWS, int BK>
-__device__ __forceinline__ void store_tile(const Stage<KM, ROWS, BK>& s, char* lds) {
-  const int t = threadIdx.x;
-#pragma unroll
-  for (int i = 0; i < Stage<KM, ROWS, BK>::N; ++i) {
-    const int idx = t + kThreads * i;
-    if (!KM) {
-      constexpr int CPR = BK / 8;
-      int row = idx / CPR, c = idx % CPR;
-      *reinterpret_cast<u32x4*>(lds + row * pitch_kc(BK) + c * 16) = s.v[i];
-    } else {
-      constexpr int CPR = ROWS / 8;
-      int kr = idx / CPR, c = idx % CPR;
-      *reinterpret_cast<u32x4*>(lds + kr * pitch_km(ROWS) + c * 16) = s.v[i];
-    }
-  }
-}
-
-// ---- LDS -> MFMA fragment ---------------------------------------------------------------
-// Fragment of 32 rows (row index = lane % 32) x 16 k (k = 8*(lane/32) .. +7) for k-step kk.
-template <bool KM, int ROWS, int BK>
-__device__ __forceinline__ bf16x8 read_frag(const char* lds, int row0, int kk) {
-  const int l = threadIdx.x & 63;
-  if (!KM) {
-    const char* p = lds + (row0 + (l & 31)) * pitch_kc(BK) + kk * 32 + (l >> 5) * 16;
-    return *reinterpret_cast<const bf16x8*>(p);
-  } else {
-    const int q = l >> 4, i = l & 15;
-    const int kr = kk * 16 + 8 * (q >> 1) + (i >> 2);
-    const int col = row0 + 16 * (q & 1) + 4 * (i & 3);
-    const char* p = lds + kr * pitch_km(ROWS) + col * 2;
-    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-        (s16x4 __attribute__((address_space(3)))*)(p));
-    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-        (s16x4 __attribute__((address_space(3)))*)(p + 4 * pitch_km(ROWS)));
-    s16x8 r = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(bf16x8, r);
-  }
-}
-
 struct Epi {
   void* out; int64_t ldo;
   void* out2;
   const uint16_t* bias;
   const float* resid; int64_t ldr;
   const uint16_t* zin;
-  float* part; // split-K partial sums
+  float* upd_w;   // EPI_F32_UPD: fp32 master tile updated in place (out2 = its bf16 weight version)
+  float eta;
 };
 
 enum { EPI_BF16 = RV_EPI_BF16, EPI_BF16_BIAS = RV_EPI_BF16_BIAS, EPI_F32_BIAS_RESID = RV_EPI_F32_BIAS_RESID,
        EPI_BF16_BIAS_GELU = RV_EPI_BF16_BIAS_GELU, EPI_BF16_DGELU = RV_EPI_BF16_DGELU, EPI_F32 = RV_EPI_F32,
-       EPI_F32_BIAS_RESID_BF16 = RV_EPI_F32_BIAS_RESID_BF16 };
+       EPI_F32_BIAS_RESID_BF16 = RV_EPI_F32_BIAS_RESID_BF16,
+       // grouped weight-gradient launch only: out f32 = acc if out is given; if upd_w is given the
+       // delayed update of Eq. 2 right here, w <- w - eta * acc (one fused multiply-add, as the
+       // stand-alone update kernel does it) and out2 bf16 = the new w
+       EPI_F32_UPD = 7 };
 
 template <int EPI>
 __device__ __forceinline__ void epilogue4(const Epi& e, int m, int n, f32x4 a) {
@@ -197,6 +111,9 @@ __device__ __forceinline__ void epilogue4(const Epi& e, int m, int n, f32x4 a) {
     u32x2 o; o.x = rv_pack_bf16x2(a.x, a.y); o.y = rv_pack_bf16x2(a.z, a.w);
     *reinterpret_cast<u32x2*>((uint16_t*)e.out + (int64_t)m * e.ldo + n) = o;
   } else if (EPI == EPI_F32) {
+    *reinterpret_cast<f32x4*>((float*)e.out + (int64_t)m * e.ldo + n) = a;
+  } else if (EPI == EPI_F32_UPD) {
+    // (no update asked for: the gradient tile alone; the update path is update_tile_staged)
     *reinterpret_cast<f32x4*>((float*)e.out + (int64_t)m * e.ldo + n) = a;
   }
 }
@@ -243,96 +160,6 @@ __device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& bm,
   const int in = id - band * GM * tiles_n;
   bm = first + in % rows;
   bn = in / rows;
-}
-
-template <int BM, int BN, int BK, int WPE, bool AKM, bool BKM, int EPI>
-__global__ __launch_bounds__(kThreads, WPE) void gemm_kernel(const uint16_t* __restrict__ A, int64_t lda,
-                                                             const uint16_t* __restrict__ B, int64_t ldb,
-                                                             int M, int N, int K, int tiles_m, int tiles_n, Epi e) {
-  constexpr int WM = BM / 2, WN = BN / 2, TM = WM / 32, TN = WN / 32, KSTEPS = BK / 16;
-  constexpr int A_BYTES = tile_bytes(AKM, BM, BK), B_BYTES = tile_bytes(BKM, BN, BK);
-  extern __shared__ __align__(16) char smem[];
-  constexpr int BUF = A_BYTES + B_BYTES;   // buffer b: A tile at b*BUF, B tile behind it
-
-  int bm, bn;
-  tile_of_block(tiles_m, tiles_n, bm, bn);
-  const int m0 = bm * BM, n0 = bn * BN;
-  const int wave = threadIdx.x >> 6, l = threadIdx.x & 63;
-  const int wm0 = (wave & 1) * WM, wn0 = (wave >> 1) * WN;
-
-  f32x16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-  Stage<AKM, BM, BK> sa;
-  Stage<BKM, BN, BK> sb;
-  init_tile<AKM, BM, BK>(sa, lda, m0, M);
-  init_tile<BKM, BN, BK>(sb, ldb, n0, N);
-  const int nk = K / BK;
-  load_tile<AKM, BM, BK>(sa, A, lda, 0);
-  load_tile<BKM, BN, BK>(sb, B, ldb, 0);
-  store_tile<AKM, BM, BK>(sa, smem);
-  store_tile<BKM, BN, BK>(sb, smem + A_BYTES);
-  __syncthreads();
-  // fragments are double buffered: the LDS reads of k-step kk+1 are in flight while the
-  // MFMAs of k-step kk issue
-  bf16x8 fa[2][TM], fb[2][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i) fa[0][i] = read_frag<AKM, BM, BK>(smem, wm0 + i * 32, 0);
-#pragma unroll
-  for (int j = 0; j < TN; ++j) fb[0][j] = read_frag<BKM, BN, BK>(smem + A_BYTES, wn0 + j * 32, 0);
-  for (int it = 0; it < nk; ++it) {
-    const int cur = it & 1;
-    const char* curA = smem + cur * BUF;
-    const char* curB = curA + A_BYTES;
-    if (it + 1 < nk) {
-      load_tile<AKM, BM, BK>(sa, A, lda, (it + 1) * BK);
-      load_tile<BKM, BN, BK>(sb, B, ldb, (it + 1) * BK);
-    }
-#pragma unroll
-    for (int kk = 0; kk < KSTEPS; ++kk) {
-      if (kk + 1 < KSTEPS) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i) fa[(kk + 1) & 1][i] = read_frag<AKM, BM, BK>(curA, wm0 + i * 32, kk + 1);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) fb[(kk + 1) & 1][j] = read_frag<BKM, BN, BK>(curB, wn0 + j * 32, kk + 1);
-      }
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk & 1][j], fa[kk & 1][i], acc[i][j], 0, 0, 0);
-      if (kk + 1 < KSTEPS) {
-        // interleave: one LDS read, then a share of the MFMAs
-        constexpr int NREAD = (AKM ? 2 : 1) * TM + (BKM ? 2 : 1) * TN;
-        constexpr int NMFMA = TM * TN;
-        constexpr int PER = NMFMA / NREAD > 0 ? NMFMA / NREAD : 1;
-#pragma unroll
-        for (int g = 0; g < NREAD; ++g) {
-          __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one DS read
-          __builtin_amdgcn_sched_group_barrier(0x008, PER, 0); // PER MFMAs
-        }
-      }
-    }
-    if (it + 1 < nk) {
-      store_tile<AKM, BM, BK>(sa, smem + (cur ^ 1) * BUF);
-      store_tile<BKM, BN, BK>(sb, smem + (cur ^ 1) * BUF + A_BYTES);
-    }
-    __syncthreads();
-    if (it + 1 < nk) {
-      const char* nA = smem + (cur ^ 1) * BUF;
-#pragma unroll
-      for (int i = 0; i < TM; ++i) fa[0][i] = read_frag<AKM, BM, BK>(nA, wm0 + i * 32, 0);
-#pragma unroll
-      for (int j = 0; j < TN; ++j) fb[0][j] = read_frag<BKM, BN, BK>(nA + A_BYTES, wn0 + j * 32, 0);
-    }
-  }
-
-  write_tile<TM, TN, EPI>(acc, e, m0 + wm0, n0 + wn0, M, N);
 }
 
 // bf16 outputs leave through LDS: every wave parks its accumulator tile (after bias / GELU /
@@ -498,6 +325,68 @@ __device__ __forceinline__ bf16x8 dtl_frag(const char* lds, int row0, int kk) {
 
 extern __shared__ __align__(1024) char dtl_smem[];
 
+// Epilogue of a weight-gradient tile with the delayed update of Eq. 2 folded in:
+//   w <- w - eta * acc (fp32 master, in place), bf16(w) into the new weight version, acc itself
+// to `out` only on request.  The master tile is fetched through LDS, half a tile at a time,
+// with direct-to-LDS loads (one instruction = one 256-column fp32 row): all rows of the half
+// are in flight together, so the read costs one memory round trip per half instead of one per
+// accumulator group, and it needs no registers.  Row pitch BN*4 + 16 bytes spreads a wave's
+// 32 rows over the banks.
+__host__ __device__ constexpr int upd_image_bytes(int bm, int bn) { return (bm / 2) * (bn * 4 + 16); }
+
+template <int BM, int BN, int NW, int TM, int TN>
+__device__ __forceinline__ void update_tile_staged(const f32x16 (&acc)[TM][TN], const Epi& e, int m0, int n0,
+                                                   int wm0, int wn0, int M, int N, char* smem) {
+  static_assert(BN == 256, "one direct-to-LDS instruction moves one 256-column fp32 row");
+  constexpr int HALF = BM / 2, PITCH = BN * 4 + 16;
+  const int wave = threadIdx.x >> 6, l = threadIdx.x & 63;
+#pragma unroll 1
+  for (int h = 0; h < 2; ++h) {
+    __syncthreads();   // LDS is free: the operand ring (h = 0) or the other half's rows (h = 1)
+    int gn = n0 + l * 4;
+    gn = gn < N ? gn : N - 4;                  // ragged tiles fetch valid memory and ignore it below
+    for (int r = wave; r < HALF; r += NW) {
+      int gm = m0 + h * HALF + r;
+      gm = gm < M ? gm : M - 1;
+      const float* src = e.upd_w + (int64_t)gm * e.ldo + gn;
+      const int m0v = __builtin_amdgcn_readfirstlane((int)(size_t)smem + r * PITCH);
+      asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                   :
+                   : "v"(src), "s"(m0v)
+                   : "memory", "m0");
+    }
+    RV_WAIT_VMCNT(0);
+    __syncthreads();
+    if (wm0 == h * HALF) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int ml = i * 32 + (l & 31);
+        const int gm = m0 + wm0 + ml;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+#pragma unroll
+          for (int rg = 0; rg < 4; ++rg) {
+            const int nl = wn0 + j * 32 + 8 * rg + 4 * (l >> 5);
+            const int gnn = n0 + nl;
+            if (gm < M && gnn < N) {
+              const f32x4 w = *reinterpret_cast<const f32x4*>(smem + ml * PITCH + nl * 4);
+              const f32x4 a = {acc[i][j][4 * rg], acc[i][j][4 * rg + 1], acc[i][j][4 * rg + 2], acc[i][j][4 * rg + 3]};
+              f32x4 r;
+              r.x = __fmaf_rn(-e.eta, a.x, w.x); r.y = __fmaf_rn(-e.eta, a.y, w.y);
+              r.z = __fmaf_rn(-e.eta, a.z, w.z); r.w = __fmaf_rn(-e.eta, a.w, w.w);
+              const int64_t o = (int64_t)gm * e.ldo + gnn;
+              *reinterpret_cast<f32x4*>(e.upd_w + o) = r;
+              u32x2 v; v.x = rv_pack_bf16x2(r.x, r.y); v.y = rv_pack_bf16x2(r.z, r.w);
+              *reinterpret_cast<u32x2*>((uint16_t*)e.out2 + o) = v;
+              if (e.out) *reinterpret_cast<f32x4*>((float*)e.out + o) = a;
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
 template <int BM, int BN, int BK, int NS, int NW, bool AKM, bool BKM, int EPI>
 __device__ __forceinline__ void gemm_dtl_body(const uint16_t* __restrict__ A, int64_t lda,
                                               const uint16_t* __restrict__ B, int64_t ldb, int M, int N,
@@ -580,10 +469,14 @@ __device__ __forceinline__ void gemm_dtl_body(const uint16_t* __restrict__ A, in
     stage = stage + 1 == NS ? 0 : stage + 1;
     fill = fill + 1 == NS ? 0 : fill + 1;
   }
-  if constexpr (staged_epi(EPI))
+  if constexpr (staged_epi(EPI)) {
     write_tile_staged<BM, BN, 64 * NW, TM, TN, EPI>(acc, e, m0, n0, wm0, wn0, M, N, smem);
-  else
+  } else if constexpr (EPI == EPI_F32_UPD) {
+    if (e.upd_w) update_tile_staged<BM, BN, NW, TM, TN>(acc, e, m0, n0, wm0, wn0, M, N, smem);   // workgroup-uniform
+    else write_tile<TM, TN, EPI>(acc, e, m0 + wm0, n0 + wn0, M, N);
+  } else {
     write_tile<TM, TN, EPI>(acc, e, m0 + wm0, n0 + wn0, M, N);
+  }
 }
 
 template <int BM, int BN, int BK, int NS, int NW, int WPE, bool AKM, bool BKM, int EPI>
@@ -600,6 +493,7 @@ __global__ __launch_bounds__(64 * NW, WPE) void gemm_dtl_kernel(const uint16_t* 
 // One launch fills the chip where four small grids would each leave most CUs idle.
 struct GroupedProblem {
   const uint16_t* A; const uint16_t* B; float* out;
+  float* upd_w; uint16_t* upd_ver; float eta;
   int lda, ldb, ldo, M, N, K, tiles_m, tiles_n, first_tile;
 };
 struct GroupedArgs {
@@ -625,8 +519,8 @@ __global__ __launch_bounds__(64 * NW, WPE) void gemm_dtl_grouped_wgrad_kernel(Gr
   const int band = local / (2 * q.tiles_n), first_row = band * 2;
   const int rows = q.tiles_m - first_row < 2 ? q.tiles_m - first_row : 2;
   const int in = local - band * 2 * q.tiles_n;
-  Epi e{q.out, q.ldo, nullptr, nullptr, nullptr, 0, nullptr, nullptr};
-  gemm_dtl_body<BM, BN, BK, NS, NW, true, true, EPI_F32>(q.A, q.lda, q.B, q.ldb, q.M, q.N, q.K, first_row + in % rows,
+  Epi e{q.out, q.ldo, q.upd_ver, nullptr, nullptr, 0, nullptr, q.upd_w, q.eta};
+  gemm_dtl_body<BM, BN, BK, NS, NW, true, true, EPI_F32_UPD>(q.A, q.lda, q.B, q.ldb, q.M, q.N, q.K, first_row + in % rows,
                                                       in / rows, e);
 }
 
@@ -635,15 +529,13 @@ rv_status launch_dtl(const rv_gemm_args& g, hipStream_t st) {
   constexpr int ring = NS * (dtl_tile_bytes(BM, BK) + dtl_tile_bytes(BN, BK));
   constexpr int image = staged_epi(EPI) ? BM * stage_pitch(BN) : 0;
   constexpr int smem = ring > image ? ring : image;
-  static bool configured = false;
   auto kern = gemm_dtl_kernel<BM, BN, BK, NS, NW, WPE, AKM, BKM, EPI>;
-  if (!configured) {
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
-      return RV_E_DEVICE;
-    configured = true;
-  }
+  // once per instantiation; a function-local static is initialised exactly once, also under threads
+  static const hipError_t configured =
+      hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+  if (configured != hipSuccess) return RV_E_DEVICE;
   int tm = (g.M + BM - 1) / BM, tn = (g.N + BN - 1) / BN;
-  Epi e{g.out, g.ldo, g.out2, g.bias, g.resid, g.ldr, g.zin, nullptr};
+  Epi e{g.out, g.ldo, g.out2, g.bias, g.resid, g.ldr, g.zin, nullptr, 0.f};
   const int ntiles = tm * tn;
   if (!(BM == 128 && BN == 128)) tm = -tm;   // measured: the XCD-banded map pays only for the small tile
   hipLaunchKernelGGL(kern, dim3(ntiles), dim3(64 * NW), smem, st, g.A, g.lda, g.B, g.ldb, g.M, g.N, g.K,
@@ -651,26 +543,7 @@ rv_status launch_dtl(const rv_gemm_args& g, hipStream_t st) {
   return rv_launch_status();
 }
 
-template <int BM, int BN, int BK, int WPE, bool AKM, bool BKM, int EPI>
-rv_status launch(const rv_gemm_args& g, hipStream_t st) {
-  constexpr int smem = 2 * (tile_bytes(AKM, BM, BK) + tile_bytes(BKM, BN, BK));
-  static bool configured = false;
-  auto kern = gemm_kernel<BM, BN, BK, WPE, AKM, BKM, EPI>;
-  if (!configured) {
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
-      return RV_E_DEVICE;
-    configured = true;
-  }
-  int tm = (g.M + BM - 1) / BM, tn = (g.N + BN - 1) / BN;
-  Epi e{g.out, g.ldo, g.out2, g.bias, g.resid, g.ldr, g.zin, nullptr};
-  const int ntiles = tm * tn;
-  if (!(BM == 128 && BN == 128)) tm = -tm;   // measured: the XCD-banded map pays only for the small tile
-  hipLaunchKernelGGL(kern, dim3(ntiles), dim3(kThreads), smem, st, g.A, g.lda, g.B, g.ldb, g.M, g.N, g.K,
-                     tm, tn, e);
-  return rv_launch_status();
-}
-
-// Tile choice (codes >= 2000: direct-to-LDS ring; others: register-staged double buffer).
+// Tile choice (codes: 5256, 2256, 2192, 2128).
 //   5256  256x256, eight waves of 128x64, BK 64, two stages, one workgroup per CU: lowest
 //         LDS traffic per MFMA, two waves per SIMD cover each other's barrier stalls;
 //   2192  128x256, four waves of 64x128, BK 32, three stages, two workgroups per CU;
@@ -696,9 +569,6 @@ rv_status pick_tile(const rv_gemm_args& g, hipStream_t st) {
     const double c256 = cost(256, 256, 1, 1.0), c192 = cost(128, 256, 2, 0.92), c128 = cost(128, 128, 2, 0.85);
     tile = c256 <= c192 && c256 <= c128 ? 5256 : (c192 <= c128 ? 2192 : 2128);
   }
-  if (tile == 256) return launch<256, 256, 64, 1, AKM, BKM, EPI>(g, st);
-  if (tile == 192) return launch<128, 256, 32, 2, AKM, BKM, EPI>(g, st);
-  if (tile == 128) return launch<128, 128, 64, 2, AKM, BKM, EPI>(g, st);
   if (tile == 2256) return launch_dtl<256, 256, 32, 4, 4, 1, AKM, BKM, EPI>(g, st);
   if (tile == 2192) return launch_dtl<128, 256, 32, 3, 4, 2, AKM, BKM, EPI>(g, st);
   if (tile == 2128) return launch_dtl<128, 128, 64, 2, 4, 2, AKM, BKM, EPI>(g, st);
@@ -712,6 +582,10 @@ rv_status rv_gemm_bf16(const rv_gemm_args& g, hipStream_t st) {
   if (!g.A || !g.B || !g.out || g.M < 8 || g.N < 8 || g.K < 64) return RV_E_INVAL;
   if (g.K % 64 || g.N % 8 || g.M % 8 || g.lda % 8 || g.ldb % 8 || g.ldo % 4) return RV_E_INVAL;
   if ((((uintptr_t)g.A) | ((uintptr_t)g.B) | ((uintptr_t)g.out)) & 15) return RV_E_INVAL;
+  // bf16 outputs (and the pre-activation input of GELU') move in 16-byte row pieces: pitch % 8
+  if ((staged_epi(g.epi) || g.epi == EPI_F32_BIAS_RESID_BF16) && g.ldo % 8) return RV_E_INVAL;
+  if (staged_epi(g.epi) && g.epi == EPI_BF16_BIAS_GELU && (((uintptr_t)g.out2) & 15)) return RV_E_INVAL;
+  if (g.epi == EPI_BF16_DGELU && (((uintptr_t)g.zin) & 15)) return RV_E_INVAL;
   // tile offsets are kept in 32 bits
   if ((int64_t)(g.a_kmajor ? g.K : g.M) * g.lda >= (1ll << 31) || (int64_t)(g.b_kmajor ? g.K : g.N) * g.ldb >= (1ll << 31))
     return RV_E_INVAL;
@@ -750,7 +624,8 @@ rv_status launch_grouped(const rv_gemm_args* gs, int count, hipStream_t st) {
   for (int k = 0; k < count; ++k) {
     const rv_gemm_args& g = gs[k];
     GroupedProblem& q = ga.p[k];
-    q.A = g.A; q.B = g.B; q.out = (float*)g.out;
+    q.A = g.A; q.B = g.B; q.out = g.store_out ? (float*)g.out : nullptr;
+    q.upd_w = g.upd_w; q.upd_ver = g.upd_ver; q.eta = g.upd_eta;
     q.lda = (int)g.lda; q.ldb = (int)g.ldb; q.ldo = (int)g.ldo; q.M = g.M; q.N = g.N; q.K = g.K;
     q.tiles_m = (g.M + BM - 1) / BM;
     q.tiles_n = (g.N + BN - 1) / BN;
@@ -759,14 +634,13 @@ rv_status launch_grouped(const rv_gemm_args* gs, int count, hipStream_t st) {
   }
   for (int k = count; k < RV_GEMM_GROUP_MAX; ++k) ga.p[k] = ga.p[0];
   ga.count = count;
-  constexpr int smem = NS * (dtl_tile_bytes(BM, BK) + dtl_tile_bytes(BN, BK));
-  static bool configured = false;
+  constexpr int ring = NS * (dtl_tile_bytes(BM, BK) + dtl_tile_bytes(BN, BK));
+  constexpr int smem = ring > upd_image_bytes(BM, BN) ? ring : upd_image_bytes(BM, BN);
+  static_assert(smem <= 160 * 1024, "LDS of one CU");
   auto kern = gemm_dtl_grouped_wgrad_kernel<BM, BN, BK, NS, NW, 2>;
-  if (!configured) {
-    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem) != hipSuccess)
-      return RV_E_DEVICE;
-    configured = true;
-  }
+  static const hipError_t configured =
+      hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+  if (configured != hipSuccess) return RV_E_DEVICE;
   hipLaunchKernelGGL(kern, dim3(tiles), dim3(64 * NW), smem, st, ga);
   return rv_launch_status();
 }
@@ -781,6 +655,9 @@ rv_status rv_gemm_wgrad_grouped(const rv_gemm_args* gs, int count, hipStream_t s
       return RV_E_INVAL;
     if ((((uintptr_t)g.A) | ((uintptr_t)g.B) | ((uintptr_t)g.out)) & 15) return RV_E_INVAL;
     if ((int64_t)g.K * g.lda >= (1ll << 31) || (int64_t)g.K * g.ldb >= (1ll << 31)) return RV_E_INVAL;
+    if ((g.upd_w != nullptr) != (g.upd_ver != nullptr)) return RV_E_INVAL;
+    if (!g.upd_w && !g.store_out) return RV_E_INVAL;
+    if ((((uintptr_t)g.upd_w) & 15) || (((uintptr_t)g.upd_ver) & 7)) return RV_E_INVAL;
   }
   // 256x256 tiles, eight waves (measured against 128x128 and 128x256 tiles, alone and inside the
   // stage step of configs 2, 3 and 5: fewest LDS bytes per MFMA, so it takes the least CU time

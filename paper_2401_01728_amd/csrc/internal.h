@@ -31,6 +31,13 @@ struct rv_gemm_args {
   //      the 256x256 tile as soon as it covers half the chip
   //   2  the same, off the critical chain: always the 256x256 tile (least CU time per flop)
   int sharing = 0;
+  // weight-gradient products of the grouped launch only: the delayed update of Eq. 2 applied in
+  // the epilogue.  upd_w = fp32 master tile base (same [M, ldo] layout as out), upd_ver = bf16
+  // weight-version tile base; the gradient itself is stored to `out` only if store_out.
+  float* upd_w = nullptr;
+  uint16_t* upd_ver = nullptr;
+  float upd_eta = 0.f;
+  bool store_out = true;
 };
 rv_status rv_gemm_bf16(const rv_gemm_args& g, hipStream_t st);
 // up to RV_GEMM_GROUP_MAX weight-gradient products (both operands k-major, fp32 output) in one launch
@@ -47,9 +54,19 @@ rv_status rv_ln_bwd(const uint16_t* dy, const float* x, const float* mean, const
                     int T, int d, hipStream_t st);
 int rv_colsum_parts(int T);   // partial rows written by rv_colsum_bf16 (each N floats)
 rv_status rv_colsum_bf16(const uint16_t* a, int64_t lda, int T, int N, float* part, hipStream_t st);
-rv_status rv_reduce_rows(const float* part, int R, int64_t pitch, int N, float* out, hipStream_t st);
+// out_k[c] = sum_r src_k[r * pitch + c].  upd (may be null): per job the fp32 master vector and the
+// bf16 weight-version vector the column sums update in place, w <- w - eta * sum (Eq. 2); with
+// store = false the sums themselves are not written.
+struct rv_reduce_update {
+  float* w[4];
+  uint16_t* ver[4];
+  float eta;
+  bool store;
+};
 rv_status rv_reduce_rows_multi(const float* const* src, float* const* out, int njobs, int R, int64_t pitch,
-                               int N, hipStream_t st);
+                               int N, hipStream_t st, const rv_reduce_update* upd = nullptr);
+rv_status rv_reduce_rows(const float* part, int R, int64_t pitch, int N, float* out, hipStream_t st,
+                         const rv_reduce_update* upd = nullptr);
 rv_status rv_bf16_to_f32(const uint16_t* a, float* o, int64_t n, hipStream_t st);
 
 // ---- attention.hip ----------------------------------------------------------------
@@ -87,8 +104,13 @@ struct rv_stage {
   float* gacc = nullptr;    // [P] fp32 sum of the gradients of the current accumulation group
   int accum = 1, acc_count = 0;   // microbatches per update; backwards so far in the group
   bool defer = false;       // backward leaves its update pending (folded into the next cluster sync)
+  bool keep_grad = false;   // decoder: also store the parameter gradient when the update is applied in the
+                            // epilogues that produce it (rv_stage_keep_grad)
+  bool fused = false;       // the running backward applies Eq. 2 in those epilogues
+  bool grad_valid = false;  // `grad` holds the whole gradient of the last backward
   size_t ver_elem = 0;      // bytes per parameter in a version slot (2 or 4)
-  std::vector<char*> ver;   // tau+1 version slots
+  std::vector<char*> ver;   // tau+2 version slots: one is always free of readers, so an update can be
+                            // written piece by piece while the backward still reads its own version
   std::vector<int> ver_ref; // in-flight microbatches bound to each slot
   int cur = 0;              // slot holding the newest version
   std::vector<rv_slot> slots;

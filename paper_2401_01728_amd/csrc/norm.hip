@@ -233,7 +233,10 @@ __global__ __launch_bounds__(kThreads) void colsum_bf16_kernel(const uint16_t* _
 // its rows in order, the eight partial sums are combined in a fixed order.
 struct ReduceJobs {
   const float* src[4];
-  float* out[4];
+  float* out[4];      // null: the sums are not stored
+  float* w[4];        // fp32 parameters updated in place with the sums (null: none), and
+  uint16_t* ver[4];   // their bf16 weight version
+  float eta;
 };
 __global__ __launch_bounds__(kThreads) void reduce_rows_kernel(ReduceJobs jobs, int R, int64_t pitch, int N) {
   __shared__ float red[8][33];
@@ -257,7 +260,12 @@ __global__ __launch_bounds__(kThreads) void reduce_rows_kernel(ReduceJobs jobs, 
     float t = red[0][cl];
 #pragma unroll
     for (int w = 1; w < 8; ++w) t += red[w][cl];
-    jobs.out[blockIdx.y][c] = t;
+    if (jobs.out[blockIdx.y]) jobs.out[blockIdx.y][c] = t;
+    if (jobs.w[blockIdx.y]) {   // delayed update of this small parameter vector (Eq. 2), where its gradient is born
+      const float r = __fmaf_rn(-jobs.eta, t, jobs.w[blockIdx.y][c]);
+      jobs.w[blockIdx.y][c] = r;
+      jobs.ver[blockIdx.y][c] = rv_f32_to_bf16(r);
+    }
   }
 }
 
@@ -322,20 +330,24 @@ rv_status rv_colsum_bf16(const uint16_t* a, int64_t lda, int T, int N, float* pa
 }
 
 rv_status rv_reduce_rows_multi(const float* const* src, float* const* out, int njobs, int R, int64_t pitch,
-                               int N, hipStream_t st) {
+                               int N, hipStream_t st, const rv_reduce_update* upd) {
   if (njobs < 1 || njobs > 4 || R < 1 || N < 1) return RV_E_INVAL;
   ReduceJobs j;
+  j.eta = upd ? upd->eta : 0.f;
   for (int k = 0; k < 4; ++k) {
     j.src[k] = k < njobs ? src[k] : nullptr;
-    j.out[k] = k < njobs ? out[k] : nullptr;
-    if (k < njobs && (!src[k] || !out[k])) return RV_E_INVAL;
+    j.out[k] = k < njobs && (!upd || upd->store) ? out[k] : nullptr;
+    j.w[k] = k < njobs && upd ? upd->w[k] : nullptr;
+    j.ver[k] = k < njobs && upd ? upd->ver[k] : nullptr;
+    if (k < njobs && (!src[k] || !out[k] || (upd && (!upd->w[k] || !upd->ver[k])))) return RV_E_INVAL;
   }
   hipLaunchKernelGGL(reduce_rows_kernel, dim3((N + 31) / 32, njobs), dim3(kThreads), 0, st, j, R, pitch, N);
   return rv_launch_status();
 }
 
-rv_status rv_reduce_rows(const float* part, int R, int64_t pitch, int N, float* out, hipStream_t st) {
-  return rv_reduce_rows_multi(&part, &out, 1, R, pitch, N, st);
+rv_status rv_reduce_rows(const float* part, int R, int64_t pitch, int N, float* out, hipStream_t st,
+                         const rv_reduce_update* upd) {
+  return rv_reduce_rows_multi(&part, &out, 1, R, pitch, N, st, upd);
 }
 
 rv_status rv_bf16_to_f32(const uint16_t* a, float* o, int64_t n, hipStream_t st) {

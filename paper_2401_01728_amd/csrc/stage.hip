@@ -1,10 +1,12 @@
 // Stage object: one peer of the paper's Alg. 1.  Host-side bookkeeping only:
 //   - the microbatch -> stash-slot map (at most tau+1 in flight: the paper's rule that a
 //     sender waits until the receiver's buffer has room becomes RV_E_STASH_FULL),
-//   - the ring of tau+1 weight versions.  A forward binds the microbatch to the newest
-//     version; its backward reads exactly that version (Eq. 2 takes the gradient at the
-//     parameters in force during the forward); the update that follows publishes a new
-//     version into a slot no in-flight microbatch refers to.
+//   - the ring of weight versions.  A forward binds the microbatch to the newest version; its
+//     backward reads exactly that version (Eq. 2 takes the gradient at the parameters in force
+//     during the forward); the update publishes a new version into a slot no in-flight
+//     microbatch refers to.  tau+1 microbatches can be in flight, each bound to a version of
+//     its own, so tau+2 slots are kept: the new version can then be written piece by piece, by
+//     the kernels that produce the gradient, while the backward still reads its own.
 // All device work is enqueued on the stage's stream by mlp.hip / decoder.hip / update.hip.
 #include <new>
 #include "internal.h"
@@ -62,13 +64,14 @@ extern "C" rv_status rv_stage_create(const rv_stage_desc* d, rv_stage** out) {
   rv_status rc = d->kind == RV_MLP ? rv_mlp_plan(s) : rv_dec_plan(s);
   if (rc != RV_OK) { free_all(s); return rc; }
   s->ver_elem = s->dtype == RV_BF16 ? 2 : 4;
-  const int ns = s->tau + 1;
-  s->ver.assign(ns, nullptr);
-  s->ver_ref.assign(ns, 0);
+  const int ns = s->tau + 1;        // stash slots
+  const int nv = s->tau + 2;        // weight versions
+  s->ver.assign(nv, nullptr);
+  s->ver_ref.assign(nv, 0);
   s->slots.assign(ns, rv_slot());
   bool ok = hipMalloc((void**)&s->master, s->P * 4) == hipSuccess &&
             hipMalloc((void**)&s->grad, s->P * 4) == hipSuccess;
-  for (int i = 0; ok && i < ns; ++i) ok = hipMalloc((void**)&s->ver[i], s->P * s->ver_elem) == hipSuccess;
+  for (int i = 0; ok && i < nv; ++i) ok = hipMalloc((void**)&s->ver[i], s->P * s->ver_elem) == hipSuccess;
   if (ok && s->slot_bytes) ok = hipMalloc((void**)&s->stash, s->slot_bytes * ns) == hipSuccess;
   if (ok && s->work_bytes) ok = hipMalloc((void**)&s->work, s->work_bytes) == hipSuccess;
   if (!ok) { (void)hipGetLastError(); free_all(s); return RV_E_NOMEM; }
@@ -166,6 +169,7 @@ extern "C" rv_status rv_cluster_sync(rv_stage* const* stages, int C, int R, int 
   }
   hipStream_t st = stages[0]->st;
   const rv_stage* p = pending >= 0 ? stages[pending] : nullptr;
+  if (p && !p->grad_valid) return RV_E_INVAL;   // no deferred gradient to fold in
   RV_TRY(rv_cluster_average(masters, C, stages[0]->P, R, nullptr, 1, p ? p->grad : nullptr, pending >= 0 ? pending : 0,
                             p ? p->eta : 0.f, st));
   for (int c = 0; c < C; ++c) {
@@ -208,8 +212,15 @@ extern "C" rv_status rv_stage_get_params(const rv_stage* s, float* flat_out, siz
   return RV_OK;
 }
 
+extern "C" rv_status rv_stage_keep_grad(rv_stage* s, int on) {
+  if (!s) return RV_E_INVAL;
+  s->keep_grad = on != 0;
+  return RV_OK;
+}
+
 extern "C" rv_status rv_stage_last_grad(const rv_stage* s, float* flat_out, size_t n) {
   if (!s || !flat_out || n != s->P) return RV_E_INVAL;
+  if (!s->grad_valid) return RV_E_INVAL;   // no backward yet, or its gradient was consumed where it was produced
   RV_HIP_TRY(hipMemcpyAsync(flat_out, s->grad, n * 4, hipMemcpyDeviceToDevice, s->st));
   return RV_OK;
 }
@@ -249,27 +260,26 @@ rv_status do_forward(rv_stage* s, int64_t mb_id, const void* in, void* out) {
   return RV_OK;
 }
 
-// backward branch + update, enqueued on s->st.  never_in_place: the update must not
-// overwrite the current version (a forward may be reading it on another stream).
-rv_status do_backward(rv_stage* s, int slot_i, const void* grad_out, void* grad_in, bool never_in_place) {
+// backward branch + update, enqueued on s->st
+rv_status do_backward(rv_stage* s, int slot_i, const void* grad_out, void* grad_in) {
   rv_slot& sl = s->slots[slot_i];
-  // The updated block is published as a new version in a slot that no in-flight microbatch
-  // will be bound to once this one has retired (with tau+1 slots and at most tau left in
-  // flight there is always one; the current slot itself if nobody else refers to it).  The
-  // slot is chosen before the backward so that a stage kind may update layer by layer as the
-  // gradients complete; a layer's weights are not read again once its gradient exists, so
-  // this is safe even when the slot is the one this backward reads.
-  // With gradient accumulation only the last microbatch of a group updates; the others leave
-  // the current version in force.
+  // The updated block is published as a new version in a slot that no in-flight microbatch is
+  // bound to - not even this one, whose version the backward is still reading while the first
+  // pieces of the new one are written (tau+2 slots, at most tau+1 of them referenced).  The slot
+  // is chosen before the backward so that a stage kind may update layer by layer as the
+  // gradients complete.  With gradient accumulation only the last microbatch of a group
+  // updates; the others leave the current version in force.
   const bool updates = !s->defer && s->acc_count + 1 >= s->accum;
   int dst = -1;
-  auto refs = [&](size_t v) { return s->ver_ref[v] - ((int)v == sl.ver ? 1 : 0); };
   if (updates) {
-    if (!never_in_place && refs(s->cur) == 0) dst = s->cur;
     for (size_t v = 0; dst < 0 && v < s->ver.size(); ++v)
-      if (refs(v) == 0 && !(never_in_place && (int)v == s->cur)) dst = (int)v;
+      if (s->ver_ref[v] == 0) dst = (int)v;
     if (dst < 0) return RV_E_DEVICE;  // unreachable by the counting argument above
   }
+  // Plain Eq. 2 on a decoder stage is applied in the epilogues that produce the gradient (the
+  // weight-gradient products, the column reductions); momentum, accumulation and deferred steps
+  // take the separate update kernels.
+  s->fused = s->kind == RV_DECODER && updates && s->accum == 1 && !s->vel;
   s->upd_dst = dst;
   rv_status rc;
   if (s->kind == RV_MLP) {
@@ -279,6 +289,7 @@ rv_status do_backward(rv_stage* s, int slot_i, const void* grad_out, void* grad_
     rc = rv_dec_backward(s, sl, grad_out, grad_in);   // updates block by block
   }
   if (rc != RV_OK) return rc;   // (a failed launch leaves the stage unusable)
+  s->grad_valid = !s->fused || s->keep_grad;
   sl.live = false;
   s->ver_ref[sl.ver] -= 1;
   sl.ver = -1;
@@ -299,7 +310,7 @@ extern "C" rv_status rv_stage_backward(rv_stage* s, int64_t mb_id, const void* g
   if (!s || !grad_out) return RV_E_INVAL;
   int i = find_slot(s, mb_id);
   if (i < 0) return RV_E_UNKNOWN_MB;
-  return do_backward(s, i, grad_out, grad_in, false);
+  return do_backward(s, i, grad_out, grad_in);
 }
 
 extern "C" rv_status rv_stage_step(rv_stage* s, int64_t fwd_mb, const void* in, void* out, int64_t bwd_mb,
@@ -308,7 +319,7 @@ extern "C" rv_status rv_stage_step(rv_stage* s, int64_t fwd_mb, const void* in, 
   if (find_slot(s, fwd_mb) >= 0) return RV_E_DUP_MB;
   if (fwd_mb == bwd_mb) {  // tau = 0: the backward needs this very forward; nothing to overlap
     RV_TRY(do_forward(s, fwd_mb, in, out));
-    return do_backward(s, find_slot(s, bwd_mb), grad_out, grad_in, false);
+    return do_backward(s, find_slot(s, bwd_mb), grad_out, grad_in);
   }
   const int bi = find_slot(s, bwd_mb);
   if (bi < 0) return RV_E_UNKNOWN_MB;
@@ -322,7 +333,7 @@ extern "C" rv_status rv_stage_step(rv_stage* s, int64_t fwd_mb, const void* in, 
   rv_status rc = do_forward(s, fwd_mb, in, out);
   if (rc == RV_OK) {
     s->st = s->aux;
-    rc = do_backward(s, bi, grad_out, grad_in, true);
+    rc = do_backward(s, bi, grad_out, grad_in);
     s->st = main_st;
   }
   s->in_step = false;

@@ -53,7 +53,7 @@ def run_schedule(L, d, H, f, S, mb, tau, n_mb, seed, eta=1e-3, grad_std=1e-3, fu
     import paper_2401_01728_amd as rv
     shapes = blocks.decoder_param_shapes(L, d, f)
     w0 = decoder_params_host(seed, L, d, f)
-    g = rv.Stage.decoder(L, d, H, f, S, mb, tau, eta)
+    g = rv.Stage.decoder(L, d, H, f, S, mb, tau, eta, keep_grad=True)
     assert g.num_params == w0.size
     g.set_params(dev(w0))
     o = ostage.Stage("decoder", tau, eta, w0, n_blocks=L, d=d, h=H, f=f)
@@ -104,12 +104,14 @@ def test_fused_step_equals_forward_then_backward(L, d, H, f, S, mb, tau):
 
 
 def test_fused_step_is_bitwise_the_two_calls():
+    """... and the update applied inside the gradient kernels (the default) gives, bit for bit, the
+    parameters of the variant that also keeps the gradient; only the latter can be read back."""
     import paper_2401_01728_amd as rv
     L, d, H, f, S, mb, tau = 2, 128, 2, 256, 128, 2, 2
     w0 = dev(decoder_params_host(9, L, d, f))
     res = []
-    for fused in (False, True):
-        g = rv.Stage.decoder(L, d, H, f, S, mb, tau, 1e-3); g.set_params(w0)
+    for fused, keep in ((False, False), (True, False), (True, True)):
+        g = rv.Stage.decoder(L, d, H, f, S, mb, tau, 1e-3, keep_grad=keep); g.set_params(w0)
         outs = []
         for t in range(8 + tau):
             j = t - tau
@@ -124,8 +126,15 @@ def test_fused_step_is_bitwise_the_two_calls():
         outs.append(g.get_params())
         torch.cuda.synchronize()
         res.append([o.clone() for o in outs])
-    for a, b in zip(*res):
-        assert torch.equal(a, b)
+        if keep:
+            assert torch.isfinite(g.last_grad()).all()
+        else:
+            with pytest.raises(rv.RvError):
+                g.last_grad()
+    for other in res[1:]:
+        assert len(other) == len(res[0])
+        for a, b in zip(res[0], other):
+            assert torch.equal(a, b)
 
 
 def test_deep_staleness_reduced_shape():
@@ -157,7 +166,7 @@ def test_backward_uses_the_stashed_version_not_the_current_one():
             self.live[mb_id] = (self.w.copy(), x, k)
             return super().backward(mb_id, dy, defer)
 
-    g = rv.Stage.decoder(L, d, H, f, S, mb, tau, eta); g.set_params(dev(w0))
+    g = rv.Stage.decoder(L, d, H, f, S, mb, tau, eta, keep_grad=True); g.set_params(dev(w0))
     o = ostage.Stage("decoder", tau, eta, w0, n_blocks=L, d=d, h=H, f=f)
     bad = CurrentWeightsStage("decoder", tau, eta, w0, n_blocks=L, d=d, h=H, f=f)
     told_apart = 0.0

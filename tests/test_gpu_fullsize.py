@@ -62,7 +62,7 @@ def test_stale_schedule_at_full_shape(name, capsys):
     if name == "config2":
         assert np.array_equal(w.cpu().numpy(), decoder_params_host(seed, L, d, f))
         assert w.numel() == 50384896
-    g = rv.Stage.decoder(L, d, H, f, S, mb, tau, eta); g.set_params(w)
+    g = rv.Stage.decoder(L, d, H, f, S, mb, tau, eta, keep_grad=True); g.set_params(w)
     t0 = time.time()
     with SeqPool(L, d, H, f, S, mb) as pool:
         o = PooledStage(pool, "decoder", tau, eta, w.cpu().numpy(), n_blocks=L, d=d, h=H, f=f)
@@ -191,9 +191,10 @@ def test_average_at_the_stage_sizes(name, C, R):
                                                    ("config5 (4 of 12 blocks)", 4, 1600, 25, 6400, 1024, 8, 4)])
 def test_fused_steps_at_bench_shapes_are_bitwise_the_sequential_calls(name, L, d, H, f, S, mb, tau):
     """rv_stage_step as bench.py times it (forward, backward chain and parameter-gradient work on
-    three streams, buffers alternating between blocks) must give, bit for bit, what the same
-    schedule gives as forward(t); backward(t - tau) on one stream - at the real shapes, where a
-    missing dependency between the streams would show."""
+    three streams, buffers alternating between blocks, the update applied inside the gradient
+    kernels without keeping the gradient) must give, bit for bit, what the same schedule gives as
+    forward(t); backward(t - tau) on one stream - at the real shapes, where a missing dependency
+    between the streams would show."""
     import paper_2401_01728_amd as rv
     from paper_2401_01728_amd.inputs import device
     w0 = dev(decoder_params_host(2, L, d, f))
@@ -202,8 +203,8 @@ def test_fused_steps_at_bench_shapes_are_bitwise_the_sequential_calls(name, L, d
     dys = [device.fill_normal_(torch.empty(mb, S, d, dtype=torch.bfloat16, device="cuda"), 2, 2000 + t, 0.0, 1e-3)
            for t in range(n)]
     res = []
-    for fused in (False, True):
-        g = rv.Stage.decoder(L, d, H, f, S, mb, tau, 1e-3); g.set_params(w0)
+    for fused, keep in ((False, True), (True, True), (True, False)):   # the last is what bench.py times
+        g = rv.Stage.decoder(L, d, H, f, S, mb, tau, 1e-3, keep_grad=keep); g.set_params(w0)
         outs = []
         for t in range(n + tau):
             j = t - tau
@@ -214,10 +215,13 @@ def test_fused_steps_at_bench_shapes_are_bitwise_the_sequential_calls(name, L, d
                     outs.append(g.forward(t, xs[t]).clone())
                 if j >= 0:
                     outs.append(g.backward(j, dys[j]).clone())
-        outs.append(g.get_params().clone()); outs.append(g.last_grad().clone())
+        outs.append(g.get_params().clone())
+        if keep:
+            outs.append(g.last_grad().clone())
         torch.cuda.synchronize()
         res.append(outs)
         del g
-    assert len(res[0]) == len(res[1])
-    for k, (a, b) in enumerate(zip(*res)):
-        assert torch.equal(a, b), (name, k)
+    assert len(res[0]) == len(res[1]) == len(res[2]) + 1
+    for other in res[1:]:
+        for k, (a, b) in enumerate(zip(res[0], other)):
+            assert torch.equal(a, b), (name, k)

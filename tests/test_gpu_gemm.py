@@ -25,7 +25,7 @@ SHAPES = [(256, 256, 64), (128, 128, 128), (512, 384, 192), (200, 320, 256), (10
 
 
 @pytest.mark.parametrize("M,N,K", SHAPES)
-@pytest.mark.parametrize("tile", [128, 192, 256, 2128, 2192, 2256, 5256])
+@pytest.mark.parametrize("tile", [2128, 2192, 2256, 5256])
 def test_forward_product_and_epilogues(M, N, K, tile):
     from paper_2401_01728_amd import kernels as k
     x, x64 = bf16_normal(1, 0, (M, K))
@@ -51,7 +51,7 @@ def test_forward_product_and_epilogues(M, N, K, tile):
 
 
 @pytest.mark.parametrize("M,N,K", SHAPES)
-@pytest.mark.parametrize("tile", [128, 192, 256, 2128, 2192, 2256, 5256])
+@pytest.mark.parametrize("tile", [2128, 2192, 2256, 5256])
 def test_input_gradient_product(M, N, K, tile):
     """dx[M, N] = dy[M, K] W^T with W stored [N, K] (its rows are the output columns)."""
     from paper_2401_01728_amd import kernels as k
@@ -68,7 +68,7 @@ def test_input_gradient_product(M, N, K, tile):
 
 
 @pytest.mark.parametrize("M,N,K", SHAPES)
-@pytest.mark.parametrize("tile", [128, 192, 256, 2128, 2192, 2256, 5256])
+@pytest.mark.parametrize("tile", [2128, 2192, 2256, 5256])
 def test_weight_gradient_product(M, N, K, tile):
     """dW[M, N] = x^T dy with x [K, M] and dy [K, N]: contraction over the slow dimension."""
     from paper_2401_01728_amd import kernels as k
@@ -95,6 +95,9 @@ def test_strided_operands_and_rejects():
         k.gemm_bf16(x, 0, w, 1, M, N, 100, k.EPI_BF16_BIAS, o, bias=b)       # K % 64
     with pytest.raises(rv.RvError):
         k.gemm_bf16(x, 1, w, 0, M, N, K, k.EPI_BF16, o)                      # unsupported layout pair
+    wide = _out((M, N + 4), torch.bfloat16)
+    with pytest.raises(rv.RvError):
+        k.gemm_bf16(x, 0, w, 1, M, N, K, k.EPI_BF16_BIAS, wide[:, :N], bias=b)   # bf16 output pitch % 8
 
 
 def test_grouped_weight_gradient_products():
