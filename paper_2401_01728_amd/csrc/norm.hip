@@ -96,18 +96,21 @@ __global__ __launch_bounds__(kThreads, NV <= 8 ? 6 : 1) void ln_fwd_kernel(const
 // column sums over the workgroup's rows into part[blk][0..2][d]:
 //   0: sum dy * xh (d gamma)   1: sum dy (d beta)   2: sum dx (bias gradient of the Linear
 //   whose output fed this residual stream).
-constexpr int kRowsPerBlock = 8;
+constexpr int kRowsPerBlock = 16;
 constexpr int kBwdWaves = 4;
 
-// Four waves per workgroup.  A row is split over CS waves, a lane owning NV 16-byte column
-// groups of it: NV = 2 and CS = 1, 2, 4 for d <= 512, 1024, 2048 keep the three column
-// accumulators and the row operands within 80 registers - one such wave per SIMD and at most
-// 16 KiB of LDS fit beside the two 200-register waves of a matrix-product kernel of another
-// stream, so the HBM-bound backward runs under the MFMA-bound products instead of waiting for
-// a free CU.  Wider rows take NV = 4, CS = 4.  The 4/CS wave groups take rows round-robin;
-// with CS > 1 the row statistics are combined through LDS (fixed order, one barrier per row,
-// two alternating slots).
-template <int CS, int NV>
+// Four waves per workgroup, all on the same rows: wave cs owns columns [cs * NV * 256, +NV * 256)
+// of every row, a lane NV 16-byte column groups of them, and RF rows are in flight at once - all
+// their operands are requested before the first is used, so a workgroup keeps RF * 10 * d bytes
+// on the way instead of one row's.  What bounds the choice is 80 registers per lane: one such
+// wave per SIMD (and a few hundred bytes of LDS) still fits beside the two ~210-register waves
+// of a matrix-product kernel of another stream, so the HBM-bound backward runs under the
+// MFMA-bound products instead of waiting for a free CU.  NV = 1, RF = 2 for d <= 1024 (RF = 4
+// spills and measured 2 % slower in the stage step); NV = 2, RF = 1 up to 2048; NV = 4 beyond
+// (no such stage is benchmarked).  Row statistics are combined
+// through LDS in a fixed order, one barrier per RF rows, two alternating slots.  The column sums
+// stay in registers for the workgroup's 16 rows and leave as one partial row per workgroup.
+template <int NV, int RF>
 __global__ __launch_bounds__(64 * kBwdWaves, NV <= 2 ? 6 : 1) void ln_bwd_kernel(const uint16_t* __restrict__ dy,
                                                                 const float* __restrict__ x,
                                                                 const float* __restrict__ mean,
@@ -116,84 +119,90 @@ __global__ __launch_bounds__(64 * kBwdWaves, NV <= 2 ? 6 : 1) void ln_bwd_kernel
                                                                 const float* dres, float* dx,
                                                                 uint16_t* __restrict__ dx_bf16,
                                                                 float* __restrict__ part, int T, int d) {
-  constexpr int RG = kBwdWaves / CS;
-  extern __shared__ __align__(16) float red[];   // [RG][d] column sums, then [2][RG][CS][2] row statistics
-  float* stat = red + RG * d;
-  const int wave = threadIdx.x >> 6, l = threadIdx.x & 63;
-  const int cs = wave % CS, rg = wave / CS;
+  constexpr int CS = kBwdWaves;
+  __shared__ float stat[2][RF][CS][2];
+  const int cs = threadIdx.x >> 6, l = threadIdx.x & 63;
   const int cbase = cs * (NV * 256) + l * 4;
-  f32x4 ag[NV], ab[NV], ax[NV];
+  f32x4 ag[NV], ab[NV], ax[NV], gam[NV];
 #pragma unroll
-  for (int i = 0; i < NV; ++i) { ag[i] = 0.f; ab[i] = 0.f; ax[i] = 0.f; }
+  for (int i = 0; i < NV; ++i) {
+    ag[i] = 0.f; ab[i] = 0.f; ax[i] = 0.f; gam[i] = 0.f;
+    const int c = cbase + 256 * i;
+    if (c < d) gam[i] = bf16x4_to_f32(*reinterpret_cast<const u32x2*>(gamma + c));
+  }
 #pragma unroll 1
-  for (int k = 0; k < kRowsPerBlock / RG; ++k) {
-    const int row = blockIdx.x * kRowsPerBlock + k * RG + rg;
-    const bool valid = row < T;
-    // the three row operands are requested together: one memory round trip per row
-    f32x4 xh[NV], dyv[NV], rs[NV];
+  for (int k = 0; k < kRowsPerBlock / RF; ++k) {
+    const int row0 = blockIdx.x * kRowsPerBlock + k * RF;
+    // every operand of the RF rows is requested here: one memory round trip per RF rows
+    f32x4 xh[RF][NV], rs[RF][NV];
+    u32x2 dyr[RF][NV];
+    float mu[RF], r[RF];
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-      const int c = cbase + 256 * i;
-      xh[i] = 0.f; dyv[i] = 0.f; rs[i] = 0.f;
-      if (valid && c < d) {
-        xh[i] = *reinterpret_cast<const f32x4*>(x + (int64_t)row * d + c);
-        rs[i] = *reinterpret_cast<const f32x4*>(dres + (int64_t)row * d + c);
-        dyv[i] = bf16x4_to_f32(*reinterpret_cast<const u32x2*>(dy + (int64_t)row * d + c));
+    for (int q = 0; q < RF; ++q) {
+      const int row = row0 + q;
+      const bool valid = row < T;
+      mu[q] = valid ? mean[row] : 0.f; r[q] = valid ? rstd[row] : 0.f;
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        const int c = cbase + 256 * i;
+        xh[q][i] = 0.f; rs[q][i] = 0.f; dyr[q][i] = u32x2{0u, 0u};
+        if (valid && c < d) {
+          xh[q][i] = *reinterpret_cast<const f32x4*>(x + (int64_t)row * d + c);
+          rs[q][i] = *reinterpret_cast<const f32x4*>(dres + (int64_t)row * d + c);
+          dyr[q][i] = *reinterpret_cast<const u32x2*>(dy + (int64_t)row * d + c);
+        }
       }
     }
-    const float mu = valid ? mean[row] : 0.f, r = valid ? rstd[row] : 0.f;
-    float s1 = 0.f, s2 = 0.f;
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-      const int c = cbase + 256 * i;
-      if (c < d) {
-        xh[i] = (xh[i] - mu) * r;
-        const f32x4 dxh = dyv[i] * bf16x4_to_f32(*reinterpret_cast<const u32x2*>(gamma + c));
-        const f32x4 t = dxh * xh[i];
-        s1 += (dxh.x + dxh.y) + (dxh.z + dxh.w);
-        s2 += (t.x + t.y) + (t.z + t.w);
-      }
-    }
-    s1 = wave_sum(s1); s2 = wave_sum(s2);
-    if (CS > 1) {
-      float* slot = stat + (k & 1) * RG * CS * 2 + rg * CS * 2;
-      if (l == 0) { slot[cs * 2] = s1; slot[cs * 2 + 1] = s2; }
-      __syncthreads();
-      s1 = slot[0]; s2 = slot[1];
-#pragma unroll
-      for (int q = 1; q < CS; ++q) { s1 += slot[q * 2]; s2 += slot[q * 2 + 1]; }
-    }
-    const float c1 = s1 / (float)d, c2 = s2 / (float)d;
-    if (valid) {
+    for (int q = 0; q < RF; ++q) {
+      float s1 = 0.f, s2 = 0.f;
 #pragma unroll
       for (int i = 0; i < NV; ++i) {
         const int c = cbase + 256 * i;
         if (c < d) {
-          const f32x4 dxh = dyv[i] * bf16x4_to_f32(*reinterpret_cast<const u32x2*>(gamma + c));
-          const f32x4 o = (dxh - c1 - xh[i] * c2) * r + rs[i];
-          *reinterpret_cast<f32x4*>(dx + (int64_t)row * d + c) = o;
-          if (dx_bf16) *reinterpret_cast<u32x2*>(dx_bf16 + (int64_t)row * d + c) = f32_to_bf16x4(o);
-          ag[i] += dyv[i] * xh[i];
-          ab[i] += dyv[i];
-          ax[i] += o;
+          xh[q][i] = (xh[q][i] - mu[q]) * r[q];
+          const f32x4 dxh = bf16x4_to_f32(dyr[q][i]) * gam[i];
+          const f32x4 t = dxh * xh[q][i];
+          s1 += (dxh.x + dxh.y) + (dxh.z + dxh.w);
+          s2 += (t.x + t.y) + (t.z + t.w);
+        }
+      }
+      s1 = wave_sum(s1); s2 = wave_sum(s2);
+      if (l == 0) { stat[k & 1][q][cs][0] = s1; stat[k & 1][q][cs][1] = s2; }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < RF; ++q) {
+      const int row = row0 + q;
+      float s1 = stat[k & 1][q][0][0], s2 = stat[k & 1][q][0][1];
+#pragma unroll
+      for (int w = 1; w < CS; ++w) { s1 += stat[k & 1][q][w][0]; s2 += stat[k & 1][q][w][1]; }
+      const float c1 = s1 / (float)d, c2 = s2 / (float)d;
+      if (row < T) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+          const int c = cbase + 256 * i;
+          if (c < d) {
+            const f32x4 dyv = bf16x4_to_f32(dyr[q][i]);
+            const f32x4 dxh = dyv * gam[i];
+            const f32x4 o = (dxh - c1 - xh[q][i] * c2) * r[q] + rs[q][i];
+            *reinterpret_cast<f32x4*>(dx + (int64_t)row * d + c) = o;
+            if (dx_bf16) *reinterpret_cast<u32x2*>(dx_bf16 + (int64_t)row * d + c) = f32_to_bf16x4(o);
+            ag[i] += dyv * xh[q][i];
+            ab[i] += dyv;
+            ax[i] += o;
+          }
         }
       }
     }
   }
-  // column sums across the RG row groups, one quantity at a time, fixed order
-  for (int qn = 0; qn < 3; ++qn) {
-    __syncthreads();
 #pragma unroll
-    for (int i = 0; i < NV; ++i) {
-      const int c = cbase + 256 * i;
-      if (c < d) *reinterpret_cast<f32x4*>(red + rg * d + c) = qn == 0 ? ag[i] : (qn == 1 ? ab[i] : ax[i]);
-    }
-    __syncthreads();
-    for (int c = threadIdx.x * 4; c < d; c += 64 * kBwdWaves * 4) {
-      f32x4 s = *reinterpret_cast<const f32x4*>(red + c);
-#pragma unroll
-      for (int w = 1; w < RG; ++w) s += *reinterpret_cast<const f32x4*>(red + w * d + c);
-      *reinterpret_cast<f32x4*>(part + ((int64_t)blockIdx.x * 3 + qn) * d + c) = s;
+  for (int i = 0; i < NV; ++i) {
+    const int c = cbase + 256 * i;
+    if (c < d) {
+      *reinterpret_cast<f32x4*>(part + ((int64_t)blockIdx.x * 3 + 0) * d + c) = ag[i];
+      *reinterpret_cast<f32x4*>(part + ((int64_t)blockIdx.x * 3 + 1) * d + c) = ab[i];
+      *reinterpret_cast<f32x4*>(part + ((int64_t)blockIdx.x * 3 + 2) * d + c) = ax[i];
     }
   }
 }
@@ -308,14 +317,11 @@ rv_status rv_ln_bwd(const uint16_t* dy, const float* x, const float* mean, const
   if (!dy || !x || !mean || !rstd || !gamma || !dres || !dx || !part || T < 1 || d < 4 || d % 4 || d > 4096)
     return RV_E_INVAL;
   dim3 grid(rv_ln_bwd_parts(T)), blk(64 * kBwdWaves);
-  const int cs = d <= 512 ? 1 : d <= 1024 ? 2 : 4;
-  const size_t smem = ((size_t)(kBwdWaves / cs) * d + 2 * kBwdWaves * 2) * sizeof(float);
-#define RV_LN_BWD(CS, NV) \
-  hipLaunchKernelGGL((ln_bwd_kernel<CS, NV>), grid, blk, smem, st, dy, x, mean, rstd, gamma, dres, dx, dx_bf16, part, T, d);
-  if (d <= 512) { RV_LN_BWD(1, 2) }
-  else if (d <= 1024) { RV_LN_BWD(2, 2) }
-  else if (d <= 2048) { RV_LN_BWD(4, 2) }
-  else { RV_LN_BWD(4, 4) }
+#define RV_LN_BWD(NV, RF) \
+  hipLaunchKernelGGL((ln_bwd_kernel<NV, RF>), grid, blk, 0, st, dy, x, mean, rstd, gamma, dres, dx, dx_bf16, part, T, d);
+  if (d <= 1024) { RV_LN_BWD(1, 2) }
+  else if (d <= 2048) { RV_LN_BWD(2, 1) }
+  else { RV_LN_BWD(4, 1) }
 #undef RV_LN_BWD
   return rv_launch_status();
 }
