@@ -74,11 +74,6 @@ rv_status rv_k_layernorm_bwd(const void* dy, const float* x, const float* mean, 
                              float* part, float* dgamma, float* dbeta, float* dbias, int T, int d,
                              void* stream);
 
-/* out fp32 [N] = column sums of a bf16 [T,N] matrix (row pitch lda); part: scratch of
- * ceil(T/128)*N floats.  N, lda % 8 == 0. */
-rv_status rv_k_colsum_bf16(const void* a, int64_t lda, int T, int N, float* part, float* out,
-                           void* stream);
-
 /*
  * Causal self-attention.  qkv bf16 [microbatch*seq, 3*d_model] (column thirds q|k|v, heads
  * contiguous inside a third); out bf16 [microbatch*seq, d_model];

@@ -135,6 +135,23 @@ __device__ __forceinline__ void store_owned(const f32x16* acc, float mul, uint16
     }
 }
 
+// Column sums of the same accumulator over the wave's 32 rows (the lanes of a half wave), into
+// dst[0 .. DH): one partial row of the bias gradient that belongs to this slice of dqkv.  The
+// sums run over the fp32 values in a fixed butterfly order (rv_half_wave_sum).
+template <int DH>
+__device__ __forceinline__ void colsum_owned(const f32x16* acc, float mul, float* __restrict__ dst) {
+  const int l = threadIdx.x & 63, grp = l >> 5;
+#pragma unroll
+  for (int dt = 0; dt < DH / 32; ++dt)
+#pragma unroll
+    for (int rg = 0; rg < 4; ++rg) {
+      f32x4 v;
+      v.x = rv_half_wave_sum(acc[dt][4 * rg] * mul); v.y = rv_half_wave_sum(acc[dt][4 * rg + 1] * mul);
+      v.z = rv_half_wave_sum(acc[dt][4 * rg + 2] * mul); v.w = rv_half_wave_sum(acc[dt][4 * rg + 3] * mul);
+      if ((l & 31) == 0) *reinterpret_cast<f32x4*>(dst + dt * 32 + 8 * rg + 4 * grp) = v;
+    }
+}
+
 // Workgroup -> (row block, head, sequence).  Causal work per row block is a ramp, and
 // consecutive workgroup ids go to the 8 XCDs in turn: the block index must be the SLOWEST
 // digit of the id, or whole XCDs get only long (or only short) blocks and the kernel lasts as
@@ -269,7 +286,8 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kv_kernel(const uint16_t* _
                                                                const float* __restrict__ lse2,
                                                                const float* __restrict__ Dv,
                                                                uint16_t* __restrict__ dqkv, int S, int d, int H,
-                                                               int nseq, float c2, float scale) {
+                                                               int nseq, float c2, float scale,
+                                                               float* __restrict__ colpart) {
   extern __shared__ __align__(16) char smem[];
   char* Qkc = smem;                         // Q tile, k-contiguous (for S = Q K^T)
   char* Qkm = Qkc + L<DH>::KC_BYTES;        // Q tile, transpose-read (for dK^T = Q^T dS)
@@ -371,6 +389,11 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_kv_kernel(const uint16_t* _
   if (!active) return;
   store_owned<DH>(dk, scale, dqkv + (tok0 + j0) * ld + d + h * DH, ld);
   store_owned<DH>(dv, 1.0f, dqkv + (tok0 + j0) * ld + 2 * d + h * DH, ld);
+  if (colpart) {   // partial row (sequence, 32-key block) of the k and v thirds of the qkv bias gradient
+    float* prow = colpart + ((tok0 + j0) / WROWS) * ld;
+    colsum_owned<DH>(dk, scale, prow + d + h * DH);
+    colsum_owned<DH>(dv, 1.0f, prow + 2 * d + h * DH);
+  }
 }
 
 // ----------------------------------------------------------------------------------------
@@ -383,7 +406,8 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_q_kernel(const uint16_t* __
                                                               const float* __restrict__ lse2,
                                                               float* __restrict__ Dv,
                                                               uint16_t* __restrict__ dqkv, int S, int d, int H,
-                                                              int nseq, float c2, float scale) {
+                                                              int nseq, float c2, float scale,
+                                                              float* __restrict__ colpart) {
   extern __shared__ __align__(16) char smem[];
   char* Kkc = smem;                         // K tile, k-contiguous (S^T = K Q^T)
   char* Kkm = Kkc + L<DH>::KC_BYTES;        // K tile, transpose-read (dQ^T = K^T dS^T)
@@ -482,6 +506,7 @@ __global__ __launch_bounds__(kThreads) void attn_bwd_q_kernel(const uint16_t* __
   }
   if (!active) return;
   store_owned<DH>(dq, scale, dqkv + (tok0 + q0) * ld + h * DH, ld);
+  if (colpart) colsum_owned<DH>(dq, scale, colpart + ((tok0 + q0) / WROWS) * ld + h * DH);   // the q third
 }
 
 template <typename K>
@@ -519,8 +544,10 @@ rv_status rv_attn_fwd(const uint16_t* qkv, uint16_t* out, float* lse2, int mb, i
   return rv_launch_status();
 }
 
+int rv_attn_colsum_parts(int mb, int S) { return mb * (S / WROWS); }
+
 rv_status rv_attn_bwd(const uint16_t* qkv, const uint16_t* out, const uint16_t* dout, const float* lse2,
-                      float* Dbuf, uint16_t* dqkv, int mb, int S, int d, int H, hipStream_t st) {
+                      float* Dbuf, uint16_t* dqkv, int mb, int S, int d, int H, hipStream_t st, float* colpart) {
   if (!qkv || !out || !dout || !lse2 || !Dbuf || !dqkv || !shape_ok(mb, S, d, H)) return RV_E_INVAL;
   const int dh = d / H;
   const float scale = 1.0f / sqrtf((float)dh);
@@ -532,17 +559,17 @@ rv_status rv_attn_bwd(const uint16_t* qkv, const uint16_t* out, const uint16_t* 
     constexpr int s2 = 2 * L<64>::KC_BYTES + L<64>::KM_BYTES;
     RV_TRY(set_smem(attn_bwd_kv_kernel<64>, s1)); RV_TRY(set_smem(attn_bwd_q_kernel<64>, s2));
     hipLaunchKernelGGL(attn_bwd_q_kernel<64>, grid, dim3(kThreads), s2, st, qkv, (int64_t)3 * d, dout, (int64_t)d,
-                       out, lse2, Dbuf, dqkv, S, d, H, mb, c2, scale);
+                       out, lse2, Dbuf, dqkv, S, d, H, mb, c2, scale, colpart);
     hipLaunchKernelGGL(attn_bwd_kv_kernel<64>, grid, dim3(kThreads), s1, st, qkv, (int64_t)3 * d, dout, (int64_t)d,
-                       lse2, Dbuf, dqkv, S, d, H, mb, c2, scale);
+                       lse2, Dbuf, dqkv, S, d, H, mb, c2, scale, colpart);
   } else {
     constexpr int s1 = 2 * (L<128>::KC_BYTES + L<128>::KM_BYTES) + 2 * TILE * 4;
     constexpr int s2 = 2 * L<128>::KC_BYTES + L<128>::KM_BYTES;
     RV_TRY(set_smem(attn_bwd_kv_kernel<128>, s1)); RV_TRY(set_smem(attn_bwd_q_kernel<128>, s2));
     hipLaunchKernelGGL(attn_bwd_q_kernel<128>, grid, dim3(kThreads), s2, st, qkv, (int64_t)3 * d, dout, (int64_t)d,
-                       out, lse2, Dbuf, dqkv, S, d, H, mb, c2, scale);
+                       out, lse2, Dbuf, dqkv, S, d, H, mb, c2, scale, colpart);
     hipLaunchKernelGGL(attn_bwd_kv_kernel<128>, grid, dim3(kThreads), s1, st, qkv, (int64_t)3 * d, dout, (int64_t)d,
-                       lse2, Dbuf, dqkv, S, d, H, mb, c2, scale);
+                       lse2, Dbuf, dqkv, S, d, H, mb, c2, scale, colpart);
   }
   return rv_launch_status();
 }

@@ -37,3 +37,19 @@ __device__ __forceinline__ uint32_t rv_pack_bf16x2(float lo, float hi) {
   const rv_f32x2 v = {lo, hi};
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, rv_bf16x2));
 }
+
+// Sum of v over the 32 lanes of each half wave, left in every lane of the half, in a fixed
+// butterfly order: four steps inside a row of 16 lanes as DPP operands of the additions
+// themselves (quad swaps, then the two mirrors - after each step every lane of the group holds
+// the group's sum), one cross-row exchange at the end.
+template <int CTRL>
+__device__ __forceinline__ float rv_dpp_add(float v) {
+  return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float rv_half_wave_sum(float v) {
+  v = rv_dpp_add<0xB1>(v);    // quad_perm [1,0,3,2]
+  v = rv_dpp_add<0x4E>(v);    // quad_perm [2,3,0,1]
+  v = rv_dpp_add<0x141>(v);   // row_half_mirror: the other quad of each 8
+  v = rv_dpp_add<0x140>(v);   // row_mirror: the other 8 of each 16
+  return v + __shfl_xor(v, 16, 64);
+}

@@ -25,7 +25,8 @@ struct DecPlan {
   // byte offsets inside the work buffer
   // (dy: three buffers, dx1 / dz / dqkv: two, so a block's weight-gradient products can run
   // beside the next block)
-  size_t w_dres, w_dy[3], w_dx1_16[2], w_dtmp, w_dz[2], w_dqkv[2], w_D, w_part_ln[2][2], w_part_cs, w_ytmp;
+  size_t w_dres, w_dy[3], w_dx1_16[2], w_dtmp, w_dz[2], w_dqkv[2], w_D, w_part_ln[2][2], w_part_dy, w_part_dz[2],
+      w_part_qkv[2], w_ytmp;
 };
 
 }  // namespace
@@ -76,10 +77,13 @@ rv_status rv_dec_plan(rv_stage* s) {
   for (size_t& o : p->w_dqkv) { o = w; w += align_up(T * 3 * d * 2); }
   p->w_D = w; w += align_up(T * H * 4);
   const size_t part_ln = (size_t)rv_ln_bwd_parts(p->T) * 3 * d;
-  const size_t part_cs = (size_t)rv_colsum_parts(p->T) * (size_t)std::max<int64_t>(3 * d, f);
   for (auto& pair : p->w_part_ln)
     for (size_t& o : pair) { o = w; w += align_up(part_ln * 4); }
-  p->w_part_cs = w; w += align_up(part_cs * 4);
+  // partial rows of the bias gradients: of the arriving gradient (32-row blocks), of dz (one per tile
+  // row of the product that makes it, at least 128 rows) and of dqkv (32-token blocks)
+  p->w_part_dy = w; w += align_up((size_t)rv_widen_parts(p->T) * d * 4);
+  for (size_t& o : p->w_part_dz) { o = w; w += align_up((size_t)((T + 127) / 128) * f * 4); }
+  for (size_t& o : p->w_part_qkv) { o = w; w += align_up((size_t)rv_attn_colsum_parts(p->mb, p->S) * 3 * d * 4); }
   p->w_ytmp = w; w += align_up(T * d * 4);
   s->work_bytes = w;
   return RV_OK;
@@ -94,14 +98,18 @@ namespace {
 
 rv_status gemm(int sharing, hipStream_t st, const void* A, int64_t lda, int akm, const void* B, int64_t ldb, int bkm, int M,
                int N, int K, int epi, void* out, int64_t ldo, void* out2 = nullptr, const void* bias = nullptr,
-               const float* resid = nullptr, const void* zin = nullptr) {
+               const float* resid = nullptr, const void* zin = nullptr, float* colpart = nullptr,
+               int* colpart_rows = nullptr) {
   rv_gemm_args g;
+  g.colpart = colpart;
   g.sharing = sharing;
   g.A = (const uint16_t*)A; g.lda = lda; g.a_kmajor = akm;
   g.B = (const uint16_t*)B; g.ldb = ldb; g.b_kmajor = bkm;
   g.M = M; g.N = N; g.K = K; g.epi = epi; g.out = out; g.ldo = ldo; g.out2 = out2;
   g.bias = (const uint16_t*)bias; g.resid = resid; g.ldr = ldo; g.zin = (const uint16_t*)zin;
-  return rv_gemm_bf16(g, st);
+  const rv_status rc = rv_gemm_bf16(g, st);
+  if (colpart_rows) *colpart_rows = g.colpart_rows;
+  return rc;
 }
 
 }  // namespace
@@ -155,8 +163,7 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
   float* dres = (float*)(s->work + p.w_dres);
   uint16_t* dtmp = (uint16_t*)(s->work + p.w_dtmp);
   float* Dbuf = (float*)(s->work + p.w_D);
-  float* part_cs = (float*)(s->work + p.w_part_cs);
-  const int ln_parts = rv_ln_bwd_parts(T), cs_parts = rv_colsum_parts(T);
+  const int ln_parts = rv_ln_bwd_parts(T);
   // fused update (plain Eq. 2): every kernel that completes a parameter gradient applies it at once
   // to the fp32 master and writes the bf16 rounding into the new weight version `vdst`
   uint16_t* vdst = s->fused ? (uint16_t*)s->ver[s->upd_dst] : nullptr;
@@ -186,14 +193,14 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
   };
 
   // gradient of the last block's output: fp32 copy for the residual path, bf16 as operand
-  RV_TRY(rv_bf16_to_f32((const uint16_t*)grad_out, dres, (int64_t)T * d, st));
+  // (summed over tokens it is also the gradient of the last block's b2: partial sums on the way)
+  float* part_dy = (float*)(s->work + p.w_part_dy);
+  RV_TRY(rv_widen_colsum((const uint16_t*)grad_out, dres, part_dy, T, d, st));
   const uint16_t* dres16 = (const uint16_t*)grad_out;
   {
-    float* gl = s->grad + (size_t)(p.L - 1) * p.per_block;
+    float* out = s->grad + (size_t)(p.L - 1) * p.per_block + p.b2;
     RV_TRY(side_begin());
-    RV_TRY(rv_colsum_bf16(dres16, d, T, d, part_cs, ws));
-    float* out = gl + p.b2;
-    RV_TRY(rv_reduce_rows(part_cs, cs_parts, d, d, out, ws, upd(&out, 1)));
+    RV_TRY(rv_reduce_rows(part_dy, rv_widen_parts(T), d, d, out, ws, upd(&out, 1)));
   }
   for (int l = p.L - 1; l >= 0; --l) {
     const int par = l & 1;
@@ -228,13 +235,16 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
     };
     // feed-forward half
     wgrad(0, g, f, dres16, d, f, d, gl + p.w2);                                                      // dW2 = g^T dy
-    RV_TRY(gemm(sh, st, dres16, d, 0, w + p.w2, d, 0, T, f, d, RV_EPI_BF16_DGELU, dz, f, nullptr, nullptr, nullptr, z));
+    // dz = (dy W2^T) * GELU'(z); its column sums (the b1 gradient) leave the same epilogue as partial rows
+    float* part_dz = (float*)(s->work + p.w_part_dz[par]);
+    int dz_parts = 0;
+    RV_TRY(gemm(sh, st, dres16, d, 0, w + p.w2, d, 0, T, f, d, RV_EPI_BF16_DGELU, dz, f, nullptr, nullptr, nullptr, z,
+                part_dz, &dz_parts));
     wgrad(1, v2, d, dz, f, d, f, gl + p.w1);                                                         // dW1 = v2^T dz
     RV_TRY(side_begin());
-    RV_TRY(rv_colsum_bf16(dz, f, T, f, part_cs, ws));
     {
       float* out = gl + p.b1;
-      RV_TRY(rv_reduce_rows(part_cs, cs_parts, f, f, out, ws, upd(&out, 1)));
+      RV_TRY(rv_reduce_rows(part_dz, dz_parts, f, f, out, ws, upd(&out, 1)));
     }
     RV_TRY(gemm(sh, st, dz, f, 0, w + p.w1, f, 0, T, d, f, RV_EPI_BF16, dtmp, d));                       // dv2 = dz W1^T
     RV_TRY(rv_ln_bwd(dtmp, x1, (const float*)(sb + p.s_m2), (const float*)(sb + p.s_r2), w + p.ln2g, dres, dres,
@@ -248,7 +258,9 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
     // attention half
     wgrad(2, a, d, dx1_16, d, d, d, gl + p.wo);                                                      // dWo = a^T dx1
     RV_TRY(gemm(sh, st, dx1_16, d, 0, w + p.wo, d, 0, T, d, d, RV_EPI_BF16, dtmp, d));                   // da = dx1 Wo^T
-    RV_TRY(rv_attn_bwd(qkv, a, dtmp, (const float*)(sb + p.s_lse), Dbuf, dqkv, p.mb, p.S, d, p.H, st));
+    // (the attention backward also leaves partial column sums of dqkv: the qkv bias gradient)
+    float* part_qkv = (float*)(s->work + p.w_part_qkv[par]);
+    RV_TRY(rv_attn_bwd(qkv, a, dtmp, (const float*)(sb + p.s_lse), Dbuf, dqkv, p.mb, p.S, d, p.H, st, part_qkv));
     wgrad(3, u, d, dqkv, 3 * d, d, 3 * d, gl + p.wqkv);                                              // dWqkv = u^T dqkv
     RV_TRY(side_begin());
     if (s->prof_on) {   // measurement aid: bracket the launch with events on its own stream
@@ -263,10 +275,9 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
     } else {
       RV_TRY(rv_gemm_wgrad_grouped(wg, 4, ws));
     }
-    RV_TRY(rv_colsum_bf16(dqkv, 3 * d, T, 3 * d, part_cs, ws));
     {
       float* out = gl + p.bqkv;
-      RV_TRY(rv_reduce_rows(part_cs, cs_parts, 3 * d, 3 * d, out, ws, upd(&out, 1)));
+      RV_TRY(rv_reduce_rows(part_qkv, rv_attn_colsum_parts(p.mb, p.S), 3 * d, 3 * d, out, ws, upd(&out, 1)));
     }
     RV_TRY(gemm(sh, st, dqkv, 3 * d, 0, w + p.wqkv, 3 * d, 0, T, d, 3 * d, RV_EPI_BF16, dtmp, d));       // du
     uint16_t* dx16 = l == 0 ? (uint16_t*)grad_in : dy_below;

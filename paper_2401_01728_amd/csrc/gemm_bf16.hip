@@ -67,6 +67,7 @@ struct Epi {
   const uint16_t* zin;
   float* upd_w;   // EPI_F32_UPD: fp32 master tile updated in place (out2 = its bf16 weight version)
   float eta;
+  float* colpart; // EPI_BF16_DGELU: partial column sums of the output, one row (pitch ldo) per tile row
 };
 
 enum { EPI_BF16 = RV_EPI_BF16, EPI_BF16_BIAS = RV_EPI_BF16_BIAS, EPI_F32_BIAS_RESID = RV_EPI_F32_BIAS_RESID,
@@ -192,6 +193,17 @@ __device__ __forceinline__ void write_tile_staged(const f32x16 (&acc)[TM][TN], c
     }
     __syncthreads();
   }
+  // GELU' epilogue: column sums of the results over this wave's rows, kept per lane while the tile
+  // is packed (the bias gradient of the Linear below the GELU, one partial row per tile row)
+  f32x4 cs[TN][4];
+  const bool want_cs = EPI == EPI_BF16_DGELU && e.colpart != nullptr;
+  float* red = reinterpret_cast<float*>(smem + BM * PITCH);   // [2 wave rows][BN], behind the image
+  if (EPI == EPI_BF16_DGELU) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int rg = 0; rg < 4; ++rg) cs[j][rg] = 0.f;
+  }
 #pragma unroll
   for (int pass = 0; pass < PASSES; ++pass) {
 #pragma unroll
@@ -217,6 +229,7 @@ __device__ __forceinline__ void write_tile_staged(const f32x16 (&acc)[TM][TN], c
               const u32x2 z = *reinterpret_cast<const u32x2*>(smem + ml * PITCH + nl * 2);
               a.x *= dgelu_f(__uint_as_float(z.x << 16)); a.y *= dgelu_f(__uint_as_float(z.x & 0xFFFF0000u));
               a.z *= dgelu_f(__uint_as_float(z.y << 16)); a.w *= dgelu_f(__uint_as_float(z.y & 0xFFFF0000u));
+              cs[j][rg] += a;
             }
           }
           u32x2 o; o.x = rv_pack_bf16x2(a.x, a.y); o.y = rv_pack_bf16x2(a.z, a.w);
@@ -224,7 +237,23 @@ __device__ __forceinline__ void write_tile_staged(const f32x16 (&acc)[TM][TN], c
         }
       }
     }
+    if (EPI == EPI_BF16_DGELU && want_cs) {   // (workgroup-uniform)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {
+          f32x4 v;
+          v.x = rv_half_wave_sum(cs[j][rg].x); v.y = rv_half_wave_sum(cs[j][rg].y);
+          v.z = rv_half_wave_sum(cs[j][rg].z); v.w = rv_half_wave_sum(cs[j][rg].w);
+          if ((l & 31) == 0)
+            *reinterpret_cast<f32x4*>(red + (wm0 ? BN : 0) + wn0 + j * 32 + 8 * rg + 4 * (l >> 5)) = v;
+        }
+    }
     __syncthreads();
+    if (EPI == EPI_BF16_DGELU && want_cs) {
+      for (int c = threadIdx.x; c < BN; c += NT)
+        if (n0 + c < N) e.colpart[(int64_t)(m0 / BM) * e.ldo + n0 + c] = red[c] + red[BN + c];
+    }
     uint16_t* dst = (uint16_t*)(pass == 0 ? e.out : e.out2);
     constexpr int CPR = BN / 8;
     for (int idx = threadIdx.x; idx < BM * CPR; idx += NT) {
@@ -519,7 +548,7 @@ __global__ __launch_bounds__(64 * NW, WPE) void gemm_dtl_grouped_wgrad_kernel(Gr
   const int band = local / (2 * q.tiles_n), first_row = band * 2;
   const int rows = q.tiles_m - first_row < 2 ? q.tiles_m - first_row : 2;
   const int in = local - band * 2 * q.tiles_n;
-  Epi e{q.out, q.ldo, q.upd_ver, nullptr, nullptr, 0, nullptr, q.upd_w, q.eta};
+  Epi e{q.out, q.ldo, q.upd_ver, nullptr, nullptr, 0, nullptr, q.upd_w, q.eta, nullptr};
   gemm_dtl_body<BM, BN, BK, NS, NW, true, true, EPI_F32_UPD>(q.A, q.lda, q.B, q.ldb, q.M, q.N, q.K, first_row + in % rows,
                                                       in / rows, e);
 }
@@ -527,7 +556,8 @@ __global__ __launch_bounds__(64 * NW, WPE) void gemm_dtl_grouped_wgrad_kernel(Gr
 template <int BM, int BN, int BK, int NS, int NW, int WPE, bool AKM, bool BKM, int EPI>
 rv_status launch_dtl(const rv_gemm_args& g, hipStream_t st) {
   constexpr int ring = NS * (dtl_tile_bytes(BM, BK) + dtl_tile_bytes(BN, BK));
-  constexpr int image = staged_epi(EPI) ? BM * stage_pitch(BN) : 0;
+  // the GELU' epilogue keeps two rows of fp32 column sums (one per wave row) behind the image
+  constexpr int image = staged_epi(EPI) ? BM * stage_pitch(BN) + (EPI == EPI_BF16_DGELU ? 2 * BN * 4 : 0) : 0;
   constexpr int smem = ring > image ? ring : image;
   auto kern = gemm_dtl_kernel<BM, BN, BK, NS, NW, WPE, AKM, BKM, EPI>;
   // once per instantiation; a function-local static is initialised exactly once, also under threads
@@ -535,7 +565,8 @@ rv_status launch_dtl(const rv_gemm_args& g, hipStream_t st) {
       hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
   if (configured != hipSuccess) return RV_E_DEVICE;
   int tm = (g.M + BM - 1) / BM, tn = (g.N + BN - 1) / BN;
-  Epi e{g.out, g.ldo, g.out2, g.bias, g.resid, g.ldr, g.zin, nullptr, 0.f};
+  Epi e{g.out, g.ldo, g.out2, g.bias, g.resid, g.ldr, g.zin, nullptr, 0.f, g.epi == EPI_BF16_DGELU ? g.colpart : nullptr};
+  g.colpart_rows = (g.M + BM - 1) / BM;
   const int ntiles = tm * tn;
   if (!(BM == 128 && BN == 128)) tm = -tm;   // measured: the XCD-banded map pays only for the small tile
   hipLaunchKernelGGL(kern, dim3(ntiles), dim3(64 * NW), smem, st, g.A, g.lda, g.B, g.ldb, g.M, g.N, g.K,

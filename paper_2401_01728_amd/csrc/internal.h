@@ -34,6 +34,11 @@ struct rv_gemm_args {
   // weight-gradient products of the grouped launch only: the delayed update of Eq. 2 applied in
   // the epilogue.  upd_w = fp32 master tile base (same [M, ldo] layout as out), upd_ver = bf16
   // weight-version tile base; the gradient itself is stored to `out` only if store_out.
+  // GELU' epilogue only: if given, fp32 [ceil(M / tile rows), ldo] partial column sums of the
+  // output (the bias gradient of the Linear whose pre-activation gradient this is), one row per
+  // tile row; the number of rows written comes back in colpart_rows
+  float* colpart = nullptr;
+  mutable int colpart_rows = 0;
   float* upd_w = nullptr;
   uint16_t* upd_ver = nullptr;
   float upd_eta = 0.f;
@@ -52,8 +57,10 @@ int rv_ln_bwd_parts(int T);   // partial rows written by rv_ln_bwd (each 3*d flo
 rv_status rv_ln_bwd(const uint16_t* dy, const float* x, const float* mean, const float* rstd,
                     const uint16_t* gamma, const float* dres, float* dx, uint16_t* dx_bf16, float* part,
                     int T, int d, hipStream_t st);
-int rv_colsum_parts(int T);   // partial rows written by rv_colsum_bf16 (each N floats)
-rv_status rv_colsum_bf16(const uint16_t* a, int64_t lda, int T, int N, float* part, hipStream_t st);
+// o fp32 [T,d] = a bf16 [T,d] widened, and part fp32 [rv_widen_parts(T), d] = column sums of a over
+// blocks of 32 rows
+int rv_widen_parts(int T);
+rv_status rv_widen_colsum(const uint16_t* a, float* o, float* part, int T, int d, hipStream_t st);
 // out_k[c] = sum_r src_k[r * pitch + c].  upd (may be null): per job the fp32 master vector and the
 // bf16 weight-version vector the column sums update in place, w <- w - eta * sum (Eq. 2); with
 // store = false the sums themselves are not written.
@@ -67,13 +74,16 @@ rv_status rv_reduce_rows_multi(const float* const* src, float* const* out, int n
                                int N, hipStream_t st, const rv_reduce_update* upd = nullptr);
 rv_status rv_reduce_rows(const float* part, int R, int64_t pitch, int N, float* out, hipStream_t st,
                          const rv_reduce_update* upd = nullptr);
-rv_status rv_bf16_to_f32(const uint16_t* a, float* o, int64_t n, hipStream_t st);
 
 // ---- attention.hip ----------------------------------------------------------------
 rv_status rv_attn_fwd(const uint16_t* qkv, uint16_t* out, float* lse2, int mb, int S, int d, int H,
                       hipStream_t st);
+// colpart (may be null): fp32 [mb*S/32, 3d] partial rows of the column sums of dqkv (the qkv
+// bias gradient), one per (sequence, 32-token block); reduce with rv_reduce_rows
+int rv_attn_colsum_parts(int mb, int S);
 rv_status rv_attn_bwd(const uint16_t* qkv, const uint16_t* out, const uint16_t* dout, const float* lse2,
-                      float* Dbuf, uint16_t* dqkv, int mb, int S, int d, int H, hipStream_t st);
+                      float* Dbuf, uint16_t* dqkv, int mb, int S, int d, int H, hipStream_t st,
+                      float* colpart = nullptr);
 
 // ---- stage bookkeeping -------------------------------------------------------------
 struct rv_slot {

@@ -4,8 +4,11 @@
 // 16-byte column groups lane*4 + 256*i, statistics are reduced with wave shuffles, the
 // residual stream and its gradient stay fp32, matrix-product operands leave as bf16.
 //
-// Column sums over tokens are produced in two deterministic steps: every workgroup
-// writes one partial row, a second kernel adds the partial rows in order.
+// Column sums over tokens (bias and LayerNorm-affine gradients) are produced in two
+// deterministic steps: the kernel that has the summands in hand - LayerNorm backward here, the
+// attention backward and the GELU' epilogue of the matrix product elsewhere - writes one partial
+// row per workgroup, and reduce_rows_kernel adds the partial rows in order (and applies the
+// delayed update to those small parameter vectors on the spot).
 #include "internal.h"
 
 namespace {
@@ -207,34 +210,25 @@ __global__ __launch_bounds__(64 * kBwdWaves, NV <= 2 ? 6 : 1) void ln_bwd_kernel
   }
 }
 
-// Column sums of a bf16 [T, N] matrix, first step: part[chunk][N], chunk = 128 rows.
-constexpr int kColRows = 128;
-__global__ __launch_bounds__(kThreads) void colsum_bf16_kernel(const uint16_t* __restrict__ a, int64_t lda,
-                                                               int T, int N, float* __restrict__ part) {
-  __shared__ float red[8][256 + 4];
-  const int cg = threadIdx.x & 31, rl = threadIdx.x >> 5;   // 32 column groups of 8, 8 row lanes
-  const int c0 = blockIdx.x * 256 + cg * 8;
-  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-  if (c0 < N) {
-    const int r_end = min(T, (int)(blockIdx.y + 1) * kColRows);
-    for (int r = blockIdx.y * kColRows + rl; r < r_end; r += 8) {
-      u32x4 v = *reinterpret_cast<const u32x4*>(a + (int64_t)r * lda + c0);
-      acc[0] += __uint_as_float(v.x << 16); acc[1] += __uint_as_float(v.x & 0xFFFF0000u);
-      acc[2] += __uint_as_float(v.y << 16); acc[3] += __uint_as_float(v.y & 0xFFFF0000u);
-      acc[4] += __uint_as_float(v.z << 16); acc[5] += __uint_as_float(v.z & 0xFFFF0000u);
-      acc[6] += __uint_as_float(v.w << 16); acc[7] += __uint_as_float(v.w & 0xFFFF0000u);
+// o = a widened to fp32, and the column sums of a over this workgroup's 32 rows as one partial
+// row (the gradient arriving at the stage's output is also the bias gradient of its last Linear,
+// summed over tokens).  A lane owns four columns.
+constexpr int kWidenRows = 32;
+__global__ __launch_bounds__(kThreads) void widen_colsum_kernel(const uint16_t* __restrict__ a, float* __restrict__ o,
+                                                                float* __restrict__ part, int T, int d) {
+  const int c = (blockIdx.x * kThreads + threadIdx.x) * 4;
+  if (c >= d) return;
+  const int r0 = blockIdx.y * kWidenRows;
+  f32x4 acc = 0.f;
+#pragma unroll 8
+  for (int r = r0; r < r0 + kWidenRows; ++r) {
+    if (r < T) {
+      const f32x4 v = bf16x4_to_f32(*reinterpret_cast<const u32x2*>(a + (int64_t)r * d + c));
+      *reinterpret_cast<f32x4*>(o + (int64_t)r * d + c) = v;
+      acc += v;
     }
   }
-#pragma unroll
-  for (int k = 0; k < 8; ++k) red[rl][cg * 8 + k] = acc[k];
-  __syncthreads();
-  const int c = blockIdx.x * 256 + threadIdx.x;
-  if (c < N) {
-    float s = red[0][threadIdx.x];
-#pragma unroll
-    for (int w = 1; w < 8; ++w) s += red[w][threadIdx.x];
-    part[(int64_t)blockIdx.y * N + c] = s;
-  }
+  *reinterpret_cast<f32x4*>(part + (int64_t)blockIdx.y * d + c) = acc;
 }
 
 // out_k[c] = sum_r src_k[r * pitch + c] for up to four (src, out) pairs in one launch
@@ -276,11 +270,6 @@ __global__ __launch_bounds__(kThreads) void reduce_rows_kernel(ReduceJobs jobs, 
       jobs.ver[blockIdx.y][c] = rv_f32_to_bf16(r);
     }
   }
-}
-
-__global__ void bf16_to_f32_kernel(const uint16_t* __restrict__ a, float* __restrict__ o, int64_t n4) {
-  int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n4) *reinterpret_cast<f32x4*>(o + 4 * i) = bf16x4_to_f32(*reinterpret_cast<const u32x2*>(a + 4 * i));
 }
 
 int nv_for(int d) { return d <= 1024 ? 4 : d <= 2048 ? 8 : d <= 4096 ? 16 : d <= 8192 ? 32 : 0; }
@@ -326,12 +315,12 @@ rv_status rv_ln_bwd(const uint16_t* dy, const float* x, const float* mean, const
   return rv_launch_status();
 }
 
-int rv_colsum_parts(int T) { return (T + kColRows - 1) / kColRows; }
+int rv_widen_parts(int T) { return (T + kWidenRows - 1) / kWidenRows; }
 
-rv_status rv_colsum_bf16(const uint16_t* a, int64_t lda, int T, int N, float* part, hipStream_t st) {
-  if (!a || !part || T < 1 || N < 8 || N % 8 || lda % 8) return RV_E_INVAL;
-  dim3 grid((N + 255) / 256, rv_colsum_parts(T));
-  hipLaunchKernelGGL(colsum_bf16_kernel, grid, dim3(kThreads), 0, st, a, lda, T, N, part);
+rv_status rv_widen_colsum(const uint16_t* a, float* o, float* part, int T, int d, hipStream_t st) {
+  if (!a || !o || !part || T < 1 || d < 4 || d % 4) return RV_E_INVAL;
+  dim3 grid((d / 4 + kThreads - 1) / kThreads, rv_widen_parts(T));
+  hipLaunchKernelGGL(widen_colsum_kernel, grid, dim3(kThreads), 0, st, a, o, part, T, d);
   return rv_launch_status();
 }
 
@@ -356,13 +345,6 @@ rv_status rv_reduce_rows(const float* part, int R, int64_t pitch, int N, float* 
   return rv_reduce_rows_multi(&part, &out, 1, R, pitch, N, st, upd);
 }
 
-rv_status rv_bf16_to_f32(const uint16_t* a, float* o, int64_t n, hipStream_t st) {
-  if (!a || !o || n < 4 || n % 4) return RV_E_INVAL;
-  const int64_t n4 = n / 4;
-  hipLaunchKernelGGL(bf16_to_f32_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, a, o, n4);
-  return rv_launch_status();
-}
-
 extern "C" rv_status rv_k_layernorm_fwd(const void* x, int x_is_bf16, float* xcopy, const void* gamma,
                                         const void* beta, void* y, float* mean, float* rstd, int T, int d,
                                         float eps, void* stream) {
@@ -383,11 +365,4 @@ extern "C" rv_status rv_k_layernorm_bwd(const void* dy, const float* x, const fl
   if (dbeta) { src[n] = part + d; out[n++] = dbeta; }
   if (dbias) { src[n] = part + 2 * d; out[n++] = dbias; }
   return n ? rv_reduce_rows_multi(src, out, n, R, 3 * (int64_t)d, d, st) : RV_OK;
-}
-
-extern "C" rv_status rv_k_colsum_bf16(const void* a, int64_t lda, int T, int N, float* part, float* out,
-                                      void* stream) {
-  hipStream_t st = (hipStream_t)stream;
-  RV_TRY(rv_colsum_bf16((const uint16_t*)a, lda, T, N, part, st));
-  return rv_reduce_rows(part, rv_colsum_parts(T), N, N, out, st);
 }

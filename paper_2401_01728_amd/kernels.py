@@ -53,14 +53,6 @@ def layernorm_bwd(dy, x, mean, rstd, gamma, dres, want_bf16=True, stream=None):
     return dx, dx16, dg, db, dbias
 
 
-def colsum_bf16(a, stream=None):
-    T, N = a.shape
-    part = torch.empty(((T + 127) // 128) * N, dtype=torch.float32, device="cuda")
-    out = torch.empty(N, dtype=torch.float32, device="cuda")
-    _check(_lib.lib().rv_k_colsum_bf16(_ptr(a), a.stride(0), T, N, _ptr(part), _ptr(out), _stream_handle(stream)))
-    return out
-
-
 def attention_fwd(qkv, mb, S, d, H, stream=None):
     out = torch.empty(mb * S, d, dtype=torch.bfloat16, device="cuda")
     lse2 = torch.empty(mb * H * S, dtype=torch.float32, device="cuda")

@@ -1,4 +1,4 @@
-"""LayerNorm, column sums and causal attention kernels vs the oracle's definitions
+"""LayerNorm and causal attention kernels vs the oracle's definitions
 (fp64 on the same bf16-rounded inputs).  Bars: bf16 outputs 4e-3 (one bf16 rounding on fp32
 arithmetic; attention 8e-3 / 1e-2: probabilities are rounded to bf16 before the second
 product), fp32 outputs 1e-5; each normwise and element by element (util.close)."""
@@ -42,13 +42,6 @@ def test_layernorm_forward_backward(T, d):
     close(host64(dg), rdg, 1e-5, "k", group="LayerNorm / column sum / attention kernels, bar 1e-5")
     close(host64(db), rdb, 1e-5, "k", group="LayerNorm / column sum / attention kernels, bar 1e-5")
     close(host64(dbias), rdx.sum(0), 1e-5, "k", group="LayerNorm / column sum / attention kernels, bar 1e-5")
-
-
-@pytest.mark.parametrize("T,N", [(128, 256), (1000, 3072), (129, 64), (7, 8), (512, 4800)])
-def test_colsum(T, N):
-    from paper_2401_01728_amd import kernels as k
-    a, a64 = bf16_normal(2, 0, (T, N))
-    close(host64(k.colsum_bf16(a)), a64.sum(0), 1e-5, "k", group="LayerNorm / column sum / attention kernels, bar 1e-5")
 
 
 def _heads(t64, mb, S, H, dh):
