@@ -212,6 +212,8 @@ def bench_stage(args, name, cpu_seconds=20.0):
     res["roofline_step"] = mfma_roofline(flops, ms * 1e3, algorithmic_flops_per_step=flops)
     del st
     torch.cuda.empty_cache()
+    if args.step_only:
+        return res
     # the same kernel launched alone (nothing else on the chip), operands with the step's distributions
     from paper_2401_01728_amd import kernels as kk
     act = lambda n: torch.empty(T, n, dtype=torch.bfloat16, device="cuda").normal_()
@@ -496,6 +498,8 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--cold", action="store_true", help="stage workloads: time right after --warmup steps (no wait for the steady state)")
     ap.add_argument("--no-write-back", action="store_true")
+    ap.add_argument("--step-only", action="store_true",
+                    help="stage workloads: the stage steps only, no kernels launched alone afterwards (counter runs)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="average / update: also run one plain 4*n-byte copy (counter calibration)")
     ap.add_argument("--no-overlap", action="store_true",
