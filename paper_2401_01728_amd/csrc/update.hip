@@ -5,7 +5,8 @@
 //
 // HBM-bound streaming kernel: reads w and g (4+4 B), writes w (4 B) and the version
 // copy (2 or 4 B) per parameter.  16-byte accesses, one vector per lane and as many workgroups
-// as tiles (measured best: 5.8 TB/s with the bf16 copy, 6.1 without).
+// as tiles (measured best: 5.8 TB/s with the bf16 copy, 6.5 without).  A decoder stage taking the
+// plain step does not come here: its update happens in the kernels that produce the gradient.
 #include "common.h"
 #include "internal.h"
 
@@ -18,7 +19,11 @@ constexpr int kThreads = 256;
 constexpr int kVec = 1;
 constexpr int kTile = kThreads * kVec * 4;
 
-// COPY: 0 none, 1 bf16, 2 fp32
+// COPY: 0 none, 1 bf16, 2 fp32.  Without the bf16 version w and g stream through with non-temporal
+// accesses (nothing is read twice; measured 76 % -> 81 % of HBM peak).  With it, only g does: every
+// non-temporal access to w or to the version measured 3-5 % slower there (73 % -> 69-70 %), and so
+// did 8 consecutive parameters per lane for a 16-byte bf16 store (the lanes of a wave must stay
+// 16 bytes apart on w and g).
 template <int COPY>
 __global__ __launch_bounds__(kThreads) void update_kernel(float* __restrict__ w,
                                                           const float* __restrict__ g, uint64_t n,
@@ -30,7 +35,8 @@ __global__ __launch_bounds__(kThreads) void update_kernel(float* __restrict__ w,
 #pragma unroll
     for (int u = 0; u < kVec; ++u) {
       uint64_t e = base + (uint64_t)(u * kThreads + threadIdx.x) * 4;
-      wv[u] = *reinterpret_cast<const f4*>(w + e);
+      if (COPY == 1) wv[u] = *reinterpret_cast<const f4*>(w + e);
+      else wv[u] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(w + e));
       gv[u] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(g + e));
     }
 #pragma unroll
@@ -41,14 +47,15 @@ __global__ __launch_bounds__(kThreads) void update_kernel(float* __restrict__ w,
       r.y = __fmaf_rn(-eta, gv[u].y, wv[u].y);
       r.z = __fmaf_rn(-eta, gv[u].z, wv[u].z);
       r.w = __fmaf_rn(-eta, gv[u].w, wv[u].w);
-      *reinterpret_cast<f4*>(w + e) = r;
+      if (COPY == 1) *reinterpret_cast<f4*>(w + e) = r;
+      else __builtin_nontemporal_store(r, reinterpret_cast<f4*>(w + e));
       if (COPY == 1) {
         u2 pk;
         pk.x = rv_pack_bf16x2(r.x, r.y);
         pk.y = rv_pack_bf16x2(r.z, r.w);
         *reinterpret_cast<u2*>(reinterpret_cast<uint16_t*>(copy) + e) = pk;
       } else if (COPY == 2) {
-        *reinterpret_cast<f4*>(reinterpret_cast<float*>(copy) + e) = r;
+        __builtin_nontemporal_store(r, reinterpret_cast<f4*>(reinterpret_cast<float*>(copy) + e));
       }
     }
     return;
