@@ -92,3 +92,109 @@ def test_deferred_backward_leaves_parameters_and_counts_no_update():
     assert np.array_equal(s.last_grad, g)
     s.install(w0 - 1.0)
     assert s.k == 1
+
+
+# ---- clusters that are chains of peers ---------------------------------------------------------
+CH = [[4, 6, 3], [3, 5, 2]]                       # two peers per cluster: 4 -> 6 -> 3 | 3 -> 5 -> 2
+CHP = [blocks.num_params(blocks.mlp_param_shapes(d)) for d in CH]
+
+
+def _chains(C, eta, w0s):
+    return [[stage.Stage("mlp", 0, eta, w0s[p], dims=CH[p]) for p in range(2)] for _ in range(C)]
+
+
+def _chain_batches(seed, n):
+    rng = np.random.default_rng(seed)
+    xs = [rng.normal(size=(5, 4)) for _ in range(n)]
+    ts = [rng.normal(size=(5, 2)) for _ in range(n)]
+    return xs, ts, (lambda m, i: (xs[m], lambda y: 2 * (y - ts[m]) / y.size))
+
+
+def _composite_grads(w0, w1, x, t):
+    """Gradient of the loss of the composed model by its definition: both peers' forward, then the
+    chain rule through the second peer into the first - coded here, not taken from ravnest.py."""
+    h = blocks.mlp_forward(w0, CH[0], x)
+    y = blocks.mlp_forward(w1, CH[1], h)
+    dh, g1 = blocks.mlp_backward(w1, CH[1], h, 2 * (y - t) / y.size)
+    _, g0 = blocks.mlp_backward(w0, CH[0], x, dh)
+    return g0, g1
+
+
+def test_one_chain_is_block_sgd_on_the_composed_model():
+    """C = 1, any kappa: the last peer steps first, the first peer's gradient is taken through the
+    last peer's parameters as they were in the forward (Eq. 2) - a separately written loop."""
+    rng = np.random.default_rng(11)
+    w0s = [rng.normal(size=n) * 0.5 for n in CHP]
+    xs, ts, fn = _chain_batches(12, 8)
+    for kappa in (1, 3, 5):
+        cl = _chains(1, 0.05, w0s)
+        ravnest.run_chains(cl, [0] * 8, kappa, 2, fn)
+        a, b = w0s[0].copy(), w0s[1].copy()
+        for m in range(8):
+            g0, g1 = _composite_grads(a, b, xs[m], ts[m])
+            a, b = a - 0.05 * g0, b - 0.05 * g1
+        assert np.allclose(cl[0][0].w, a, rtol=0, atol=1e-13)
+        assert np.allclose(cl[0][1].w, b, rtol=0, atol=1e-13)
+
+
+def test_chains_over_many_iterations_follow_eq17_block_by_block():
+    """120 peer iterations over 4 clusters of 2 peers, kappa = 7: at every iteration the mean of a
+    peer position over the clusters moves by -(eta/C) g on the block of the peer that ran and not
+    at all on the other block (Eq. 4, Eq. 17); after an averaging iteration all clusters agree on
+    every block; between them only the sampled peer moves."""
+    rng = np.random.default_rng(13)
+    C, eta, kappa, n = 4, 0.04, 7, 60
+    w0s = [rng.normal(size=k) * 0.5 for k in CHP]
+    xs, ts, fn = _chain_batches(14, n)
+    cl = _chains(C, eta, w0s)
+    picks = [int(v) for v in rng.integers(0, C, size=n)]
+    means = [w.copy() for w in w0s]
+    seen = {"t": 0, "syncs": 0}
+    before = {}
+
+    def snapshot():
+        for c in range(C):
+            for p in range(2):
+                before[(c, p)] = cl[c][p].w.copy()
+
+    def on_event(t, i, p, sync):
+        assert t == seen["t"]
+        seen["t"] += 1
+        seen["syncs"] += int(sync)
+        means[p] = means[p] - (eta / C) * cl[i][p].last_grad
+        for q in range(2):
+            got = sum(cl[c][q].w for c in range(C)) / C
+            assert np.allclose(got, means[q], rtol=0, atol=1e-12)
+        if sync:
+            for q in range(2):
+                for c in range(1, C):
+                    assert np.array_equal(cl[c][q].w, cl[0][q].w)
+        else:
+            for c in range(C):
+                for q in range(2):
+                    if (c, q) != (i, p):
+                        assert np.array_equal(cl[c][q].w, before[(c, q)])
+        snapshot()
+
+    snapshot()
+    ravnest.run_chains(cl, picks, kappa, 3, fn, on_event)
+    assert seen["t"] == 2 * n == 120 and seen["syncs"] == 120 // kappa
+
+
+def test_state_averaging_takes_the_mean_of_the_momentum_buffers():
+    rng = np.random.default_rng(15)
+    C, eta = 3, 0.05
+    w0 = rng.normal(size=P) * 0.5
+    st = [stage.Stage("mlp", 0, eta, w0, dims=DIMS, momentum=0.9, weight_decay=1e-3) for _ in range(C)]
+    for t in range(4):                                            # local steps part the clusters
+        for i, s in enumerate(st):
+            x = rng.normal(size=(5, 4)); dy = rng.normal(size=(5, 3))
+            s.forward(t, x); s.backward(t, dy)
+    vbar = sum(s.v for s in st) / C; wbar = sum(s.w for s in st) / C
+    ravnest.cluster_sync(st, 2, average_state=True)
+    for s in st:
+        assert np.allclose(s.v, vbar, rtol=0, atol=1e-15) and np.allclose(s.w, wbar, rtol=0, atol=1e-15)
+    # without the flag the buffers are left alone
+    v_keep = [s.v.copy() for s in st]
+    ravnest.cluster_sync(st, 2)
+    assert all(np.array_equal(s.v, v) for s, v in zip(st, v_keep))
