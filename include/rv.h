@@ -197,6 +197,25 @@ rv_status rv_block_update(float* w, const float* g, size_t n, float eta, void* b
 rv_status rv_stage_defer_update(rv_stage* s, int on);
 rv_status rv_cluster_sync(rv_stage* const* stages, int C, int R, int pending);
 
+/*
+ * The same all-reduce started on ANOTHER stream, so that the stages' own stream keeps working
+ * beside it (the clusters of the paper do not stop while their parameters are averaged):
+ * rv_cluster_sync_fork orders the averaging behind everything enqueued on the stages' stream so
+ * far and enqueues it on sync_stream (hipStream_t; the stages' own stream is allowed and gives
+ * rv_cluster_sync); the mean is written into version slots no microbatch is bound to.  Until
+ * rv_cluster_sync_join, forwards are legal on every stage and run at the version in force before
+ * the averaging (one more update of staleness for those microbatches, exactly as if they had been
+ * forwarded just before it); backward / step / set_params / get_params / set_optimizer return
+ * RV_E_INVAL.  rv_cluster_sync_join makes the stages' stream wait for the averaging and the mean
+ * the current weight version.  A cluster that is a chain of peers is averaged by one fork / join
+ * pair per peer position.
+ * flags bit 0: also average the optimiser state (the momentum buffers of rv_stage_set_optimizer,
+ * required on every stage then) in the same cycle; not combinable with a pending step.
+ */
+rv_status rv_cluster_sync_fork(rv_stage* const* stages, int C, int R, int pending, int flags,
+                               void* sync_stream);
+rv_status rv_cluster_sync_join(rv_stage* const* stages, int C);
+
 /* The momentum / weight-decay step above on bare vectors; v (device [n]) is read and updated. */
 rv_status rv_block_update_momentum(float* w, const float* g, float* v, size_t n, float eta, float momentum,
                                    float weight_decay, void* bf16_out, void* stream);

@@ -28,6 +28,8 @@ SYMBOLS = {
     "rv_stage_set_accumulation": (c_int, [c_void_p, c_int]),
     "rv_stage_defer_update": (c_int, [c_void_p, c_int]),
     "rv_cluster_sync": (c_int, [c_void_p, c_int, c_int, c_int]),
+    "rv_cluster_sync_fork": (c_int, [c_void_p, c_int, c_int, c_int, c_int, c_void_p]),
+    "rv_cluster_sync_join": (c_int, [c_void_p, c_int]),
     "rv_stage_get_params": (c_int, [c_void_p, c_void_p, c_size_t]),
     "rv_stage_last_grad": (c_int, [c_void_p, c_void_p, c_size_t]),
     "rv_stage_keep_grad": (c_int, [c_void_p, c_int]),

@@ -189,6 +189,18 @@ def cluster_sync(stages, R, pending=-1):
     _check(_lib.lib().rv_cluster_sync(arr, len(stages), R, pending))
 
 
+def cluster_sync_fork(stages, R, pending=-1, average_state=False, stream=None):
+    """rv_cluster_sync_fork: the averaging on `stream` (a torch stream) beside the stages' own."""
+    arr = (ctypes.c_void_p * len(stages))(*[s._h for s in stages])
+    _check(_lib.lib().rv_cluster_sync_fork(arr, len(stages), R, pending, 1 if average_state else 0,
+                                           _stream_handle(stream)))
+
+
+def cluster_sync_join(stages):
+    arr = (ctypes.c_void_p * len(stages))(*[s._h for s in stages])
+    _check(_lib.lib().rv_cluster_sync_join(arr, len(stages)))
+
+
 def cluster_average(replicas, R, mean_out=None, write_back=False, grad=None, grad_replica=0, eta=0.0,
                     stream=None, ring_offsets=None):
     """rv_cluster_average over a list of fp32 device vectors (rv_cluster_average_v when

@@ -129,6 +129,11 @@ struct rv_stage {
   char* work = nullptr;     // scratch shared by all calls of this stage
   size_t work_bytes = 0;
   void* impl = nullptr;     // kind-specific plan (offsets, shapes)
+  // rv_cluster_sync_fork .. join: the version slot the averaging is writing on another stream
+  // (-1: none), and the stage whose ev_sync_done closes it
+  int sync_dst = -1;
+  rv_stage* sync_owner = nullptr;
+  hipEvent_t ev_sync_ready = nullptr, ev_sync_done = nullptr;
   // rv_stage_profile: event pairs around every launch of the block's grouped weight-gradient
   // product, on the stream it is launched on
   bool prof_on = false;

@@ -25,6 +25,8 @@ void free_all(rv_stage* s) {
   if (!s) return;
   if (s->kind == RV_MLP) rv_mlp_free(s); else rv_dec_free(s);
   for (hipEvent_t ev : s->prof_ev) if (ev) (void)hipEventDestroy(ev);
+  if (s->ev_sync_ready) (void)hipEventDestroy(s->ev_sync_ready);
+  if (s->ev_sync_done) (void)hipEventDestroy(s->ev_sync_done);
   if (s->ev_fork) (void)hipEventDestroy(s->ev_fork);
   if (s->ev_join) (void)hipEventDestroy(s->ev_join);
   if (s->aux) (void)hipStreamDestroy(s->aux);
@@ -87,7 +89,9 @@ extern "C" rv_status rv_stage_create(const rv_stage_desc* d, rv_stage** out) {
       hipStreamCreateWithFlags(&s->wgs, hipStreamNonBlocking) != hipSuccess ||
       hipEventCreateWithFlags(&s->ev_wg_ready, hipEventDisableTiming) != hipSuccess ||
       hipEventCreateWithFlags(&s->ev_wg_done[0], hipEventDisableTiming) != hipSuccess ||
-      hipEventCreateWithFlags(&s->ev_wg_done[1], hipEventDisableTiming) != hipSuccess) {
+      hipEventCreateWithFlags(&s->ev_wg_done[1], hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&s->ev_sync_ready, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&s->ev_sync_done, hipEventDisableTiming) != hipSuccess) {
     free_all(s); return RV_E_DEVICE;
   }
   s->cur = 0;
@@ -114,14 +118,14 @@ extern "C" int rv_stage_in_flight(const rv_stage* s) {
 }
 
 extern "C" rv_status rv_stage_set_params(rv_stage* s, const float* flat, size_t n) {
-  if (!s || !flat || n != s->P) return RV_E_INVAL;
+  if (!s || !flat || n != s->P || s->sync_dst >= 0) return RV_E_INVAL;
   if (rv_stage_in_flight(s) != 0) return RV_E_INVAL;
   RV_HIP_TRY(hipMemcpyAsync(s->master, flat, n * 4, hipMemcpyDeviceToDevice, s->st));
   return rv_launch_publish(s->master, s->P, s->ver[s->cur], copy_kind(s), s->st);
 }
 
 extern "C" rv_status rv_stage_set_optimizer(rv_stage* s, float momentum, float weight_decay) {
-  if (!s || !(momentum >= 0.f) || !(weight_decay >= 0.f)) return RV_E_INVAL;
+  if (!s || !(momentum >= 0.f) || !(weight_decay >= 0.f) || s->sync_dst >= 0) return RV_E_INVAL;
   if (rv_stage_in_flight(s) != 0) return RV_E_INVAL;
   if (!s->vel) {
     if (hipMalloc((void**)&s->vel, s->P * 4) != hipSuccess) { (void)hipGetLastError(); s->vel = nullptr; return RV_E_NOMEM; }
@@ -149,35 +153,78 @@ extern "C" rv_status rv_stage_defer_update(rv_stage* s, int on) {
   return RV_OK;
 }
 
-extern "C" rv_status rv_cluster_sync(rv_stage* const* stages, int C, int R, int pending) {
-  if (!stages || C < 1 || C > 64 || R < 1 || pending < -1 || pending >= C) return RV_E_INVAL;
+extern "C" rv_status rv_cluster_sync_fork(rv_stage* const* stages, int C, int R, int pending, int flags,
+                                          void* sync_stream) {
+  if (!stages || C < 1 || C > 64 || R < 1 || pending < -1 || pending >= C || (flags & ~1)) return RV_E_INVAL;
+  const bool state = (flags & 1) != 0;
+  if (state && pending >= 0) return RV_E_INVAL;   // the folded step is the plain one of Alg. 2
   float* masters[64];
+  float* vels[64];
   for (int c = 0; c < C; ++c) {
     rv_stage* s = stages[c];
     if (!s || s->P != stages[0]->P || s->dtype != stages[0]->dtype || s->st != stages[0]->st) return RV_E_INVAL;
     for (int k = 0; k < c; ++k) if (stages[k] == s) return RV_E_INVAL;
     if (s->accum > 1 && s->acc_count != 0) return RV_E_INVAL;   // a gradient group is open
+    if (s->sync_dst >= 0) return RV_E_INVAL;                    // an averaging is already under way
+    if (state && !s->vel) return RV_E_INVAL;
     masters[c] = s->master;
+    vels[c] = s->vel;
   }
-  // every stage needs a version slot that no in-flight microbatch is bound to
+  // Every stage needs a version slot that no in-flight microbatch is bound to - and not the
+  // current one, which forwards issued before the join still bind to.  With tau+2 slots one
+  // exists unless tau+1 microbatches are in flight; then no forward can be admitted before the
+  // join (its stash is full) and the current slot, if unreferenced, may be overwritten.
   int dst[64];
   for (int c = 0; c < C; ++c) {
     rv_stage* s = stages[c];
-    dst[c] = s->ver_ref[s->cur] == 0 ? s->cur : -1;
-    for (size_t v = 0; dst[c] < 0 && v < s->ver.size(); ++v) if (s->ver_ref[v] == 0) dst[c] = (int)v;
+    dst[c] = -1;
+    for (size_t v = 0; dst[c] < 0 && v < s->ver.size(); ++v)
+      if (s->ver_ref[v] == 0 && (int)v != s->cur) dst[c] = (int)v;
+    if (dst[c] < 0 && s->ver_ref[s->cur] == 0 && rv_stage_in_flight(s) > s->tau) dst[c] = s->cur;
     if (dst[c] < 0) return RV_E_STASH_FULL;
   }
-  hipStream_t st = stages[0]->st;
   const rv_stage* p = pending >= 0 ? stages[pending] : nullptr;
   if (p && !p->grad_valid) return RV_E_INVAL;   // no deferred gradient to fold in
-  RV_TRY(rv_cluster_average(masters, C, stages[0]->P, R, nullptr, 1, p ? p->grad : nullptr, pending >= 0 ? pending : 0,
-                            p ? p->eta : 0.f, st));
+  rv_stage* owner = stages[0];
+  hipStream_t st = owner->st, ss = (hipStream_t)sync_stream;
+  const bool forked = ss != st;
+  if (forked) {   // the averaging follows everything enqueued on the stages' stream so far
+    RV_HIP_TRY(hipEventRecord(owner->ev_sync_ready, st));
+    RV_HIP_TRY(hipStreamWaitEvent(ss, owner->ev_sync_ready, 0));
+  }
+  RV_TRY(rv_cluster_average(masters, C, owner->P, R, nullptr, 1, p ? p->grad : nullptr, pending >= 0 ? pending : 0,
+                            p ? p->eta : 0.f, ss));
+  if (state) RV_TRY(rv_cluster_average(vels, C, owner->P, R, nullptr, 1, nullptr, 0, 0.f, ss));
   for (int c = 0; c < C; ++c) {
     rv_stage* s = stages[c];
-    RV_TRY(rv_launch_publish(s->master, s->P, s->ver[dst[c]], copy_kind(s), st));
-    s->cur = dst[c];
+    RV_TRY(rv_launch_publish(s->master, s->P, s->ver[dst[c]], copy_kind(s), ss));
+  }
+  if (forked) RV_HIP_TRY(hipEventRecord(owner->ev_sync_done, ss));
+  for (int c = 0; c < C; ++c) {
+    stages[c]->sync_dst = dst[c];
+    stages[c]->sync_owner = forked ? owner : nullptr;
   }
   return RV_OK;
+}
+
+extern "C" rv_status rv_cluster_sync_join(rv_stage* const* stages, int C) {
+  if (!stages || C < 1 || C > 64) return RV_E_INVAL;
+  for (int c = 0; c < C; ++c)
+    if (!stages[c] || stages[c]->sync_dst < 0) return RV_E_INVAL;
+  for (int c = 0; c < C; ++c) {
+    rv_stage* s = stages[c];
+    if (s->sync_owner) RV_HIP_TRY(hipStreamWaitEvent(s->st, s->sync_owner->ev_sync_done, 0));
+    s->cur = s->sync_dst;      // the mean is the newest weight version from here on
+    s->sync_dst = -1;
+    s->sync_owner = nullptr;
+  }
+  return RV_OK;
+}
+
+extern "C" rv_status rv_cluster_sync(rv_stage* const* stages, int C, int R, int pending) {
+  if (!stages || C < 1 || !stages[0]) return RV_E_INVAL;
+  RV_TRY(rv_cluster_sync_fork(stages, C, R, pending, 0, stages[0]->st));
+  return rv_cluster_sync_join(stages, C);
 }
 
 extern "C" rv_status rv_stage_profile(rv_stage* s, int on) {
@@ -207,7 +254,7 @@ extern "C" rv_status rv_stage_profile_read(rv_stage* s, int* launches, float* me
 }
 
 extern "C" rv_status rv_stage_get_params(const rv_stage* s, float* flat_out, size_t n) {
-  if (!s || !flat_out || n != s->P) return RV_E_INVAL;
+  if (!s || !flat_out || n != s->P || s->sync_dst >= 0) return RV_E_INVAL;
   RV_HIP_TRY(hipMemcpyAsync(flat_out, s->master, n * 4, hipMemcpyDeviceToDevice, s->st));
   return RV_OK;
 }
@@ -308,6 +355,7 @@ extern "C" rv_status rv_stage_forward(rv_stage* s, int64_t mb_id, const void* in
 
 extern "C" rv_status rv_stage_backward(rv_stage* s, int64_t mb_id, const void* grad_out, void* grad_in) {
   if (!s || !grad_out) return RV_E_INVAL;
+  if (s->sync_dst >= 0) return RV_E_INVAL;   // the parameters are being averaged on another stream
   int i = find_slot(s, mb_id);
   if (i < 0) return RV_E_UNKNOWN_MB;
   return do_backward(s, i, grad_out, grad_in);
@@ -315,7 +363,7 @@ extern "C" rv_status rv_stage_backward(rv_stage* s, int64_t mb_id, const void* g
 
 extern "C" rv_status rv_stage_step(rv_stage* s, int64_t fwd_mb, const void* in, void* out, int64_t bwd_mb,
                                    const void* grad_out, void* grad_in) {
-  if (!s || !in || !out || !grad_out) return RV_E_INVAL;
+  if (!s || !in || !out || !grad_out || s->sync_dst >= 0) return RV_E_INVAL;
   if (find_slot(s, fwd_mb) >= 0) return RV_E_DUP_MB;
   if (fwd_mb == bwd_mb) {  // tau = 0: the backward needs this very forward; nothing to overlap
     RV_TRY(do_forward(s, fwd_mb, in, out));
