@@ -17,6 +17,20 @@ import numpy as np
 from . import blocks
 
 
+def sgd_step(w, g, eta):
+    """Eq. 2 on a block: x <- x - eta * g."""
+    return w - eta * g
+
+
+def momentum_step(w, g, v, eta, momentum, weight_decay):
+    """The optimiser of the paper's single-cluster experiments (section 4.1: SGD with momentum and
+    weight decay), taken in its usual form d = g + wd w; v <- mu v + d; w <- w - eta v.
+    Returns (w, v)."""
+    d = g + weight_decay * w
+    v = momentum * v + d
+    return w - eta * v, v
+
+
 class StashFull(Exception):
     pass
 
@@ -89,11 +103,9 @@ class Stage:
         self.g_sum = np.zeros_like(self.w)
         self.n_sum = 0
         if self.momentum == 0.0 and self.weight_decay == 0.0:
-            self.w = self.w - self.eta * g                      # Eq. 2
+            self.w = sgd_step(self.w, g, self.eta)              # Eq. 2
         else:
-            d = g + self.weight_decay * self.w
-            self.v = self.momentum * self.v + d
-            self.w = self.w - self.eta * self.v
+            self.w, self.v = momentum_step(self.w, g, self.v, self.eta, self.momentum, self.weight_decay)
         self.k += 1
         return dx
 

@@ -1,8 +1,9 @@
-"""rv_block_update vs the definition w - eta*g in fp64 (paper Eq. 2), bar 1e-6."""
+"""rv_block_update vs the oracle's update (oracle/stage.py: Eq. 2 and its momentum variant) in fp64, bar 1e-6."""
 import numpy as np
 import pytest
 import torch
 
+from oracle import stage as ostage
 from paper_2401_01728_amd.inputs import gen
 from util import dev
 
@@ -20,7 +21,7 @@ def test_update(n, with_bf16):
     copy = torch.zeros(n, dtype=torch.bfloat16, device="cuda") if with_bf16 else None
     rv.block_update(dw, dg, eta, bf16_out=copy)
     got = dw.cpu().numpy()
-    ref = w.astype(np.float64) - np.float64(np.float32(eta)) * g.astype(np.float64)
+    ref = ostage.sgd_step(w.astype(np.float64), g.astype(np.float64), np.float64(np.float32(eta)))
     assert np.all(np.abs(got - ref) <= 1e-6 * (np.abs(w) + eta * np.abs(g)))
     assert np.array_equal(dg.cpu().numpy(), g)
     if with_bf16:
@@ -36,7 +37,7 @@ def test_update_unaligned():
     vw, vg = bw[1:1 + n], bg[3:3 + n]
     vw.copy_(dev(w)); vg.copy_(dev(g))
     rv.block_update(vw, vg, 0.25)
-    ref = w.astype(np.float64) - 0.25 * g.astype(np.float64)
+    ref = ostage.sgd_step(w.astype(np.float64), g.astype(np.float64), 0.25)
     assert np.all(np.abs(vw.cpu().numpy() - ref) <= 1e-6 * (np.abs(w) + 0.25 * np.abs(g)))
     assert bw[0].item() == 0 and bw[n + 1].item() == 0
 
@@ -51,8 +52,7 @@ def test_momentum_update(n):
     copy = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
     rv.block_update_momentum(dw, dg, dv, eta, mu, wd, bf16_out=copy)
     f = lambda a: np.float64(np.float32(a))
-    v_ref = f(mu) * v.astype(np.float64) + (g.astype(np.float64) + f(wd) * w.astype(np.float64))
-    w_ref = w.astype(np.float64) - f(eta) * v_ref
+    w_ref, v_ref = ostage.momentum_step(w.astype(np.float64), g.astype(np.float64), v.astype(np.float64), f(eta), f(mu), f(wd))
     gv, gw = dv.cpu().numpy(), dw.cpu().numpy()
     assert np.all(np.abs(gv - v_ref) <= 1e-6 * (np.abs(v) + np.abs(g) + wd * np.abs(w)))
     assert np.all(np.abs(gw - w_ref) <= 1e-6 * (np.abs(w) + eta * np.abs(v_ref)))
