@@ -286,8 +286,8 @@ struct Dtl {
 };
 
 template <bool KM, int ROWS, int BK, int NW>
-__device__ __forceinline__ void dtl_init(Dtl<KM, ROWS, BK, NW>& s, int64_t ld, int r0, int rows) {
-  const int wave = threadIdx.x >> 6, l = threadIdx.x & 63;
+__device__ __forceinline__ void dtl_init(Dtl<KM, ROWS, BK, NW>& s, int64_t ld, int r0, int rows, int wave) {
+  const int l = threadIdx.x & 63;
 #pragma unroll
   for (int i = 0; i < Dtl<KM, ROWS, BK, NW>::N; ++i) {
     const int slot = (i * NW + wave) * 64 + l;
@@ -309,9 +309,8 @@ __device__ __forceinline__ void dtl_init(Dtl<KM, ROWS, BK, NW>& s, int64_t ld, i
 
 template <bool KM, int ROWS, int BK, int NW>
 __device__ __forceinline__ void dtl_issue(const Dtl<KM, ROWS, BK, NW>& s, const uint16_t* __restrict__ g,
-                                          int64_t ld, int k0, char* lds) {
+                                          int64_t ld, int k0, char* lds, int wave) {
   const uint16_t* base = KM ? g + (int64_t)k0 * ld : g + k0;
-  const int wave = threadIdx.x >> 6;
 #pragma unroll
   for (int i = 0; i < Dtl<KM, ROWS, BK, NW>::N; ++i) {
     // LDS byte address of this wave's 1 KiB block (wave-uniform, goes to M0; the hardware
@@ -424,7 +423,13 @@ __device__ __forceinline__ void gemm_dtl_body(const uint16_t* __restrict__ A, in
   constexpr int WM = BM / 2, WN = BN / (NW / 2), TM = WM / 32, TN = WN / 32, KSTEPS = BK / 16;
   constexpr int A_BYTES = dtl_tile_bytes(BM, BK), B_BYTES = dtl_tile_bytes(BN, BK);
   constexpr int BUF = A_BYTES + B_BYTES;
-  constexpr int LPT = Dtl<AKM, BM, BK, NW>::N + Dtl<BKM, BN, BK, NW>::N;   // loads per lane per tile
+  // With eight waves and a two-stage ring the waves take turns feeding it: in even k-iterations
+  // waves 0-3 issue ALL loads of the next tile and waves 4-7 go straight to their MFMAs, in odd
+  // ones the other way round.  Waves w and w+4 share a SIMD, so while one of them is held up
+  // handing its loads to the memory pipeline the other keeps the matrix core busy.
+  constexpr bool TURNS = NW == 8 && NS == 2;
+  constexpr int NL = TURNS ? 4 : NW;                                        // loader waves per tile
+  constexpr int LPT = Dtl<AKM, BM, BK, NL>::N + Dtl<BKM, BN, BK, NL>::N;   // loads per lane per tile
   static_assert(LPT * (NS - 2) < 64, "vmcnt range");
   char* smem = dtl_smem;
 
@@ -440,16 +445,18 @@ __device__ __forceinline__ void gemm_dtl_body(const uint16_t* __restrict__ A, in
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  Dtl<AKM, BM, BK, NW> da;
-  Dtl<BKM, BN, BK, NW> db;
-  dtl_init<AKM, BM, BK, NW>(da, lda, m0, M);
-  dtl_init<BKM, BN, BK, NW>(db, ldb, n0, N);
+  const int lw = wave % NL;            // this wave's share of a tile's loads
+  const int turn = wave / NL;          // 0 or 1 with TURNS, else 0
+  Dtl<AKM, BM, BK, NL> da;
+  Dtl<BKM, BN, BK, NL> db;
+  dtl_init<AKM, BM, BK, NL>(da, lda, m0, M, lw);
+  dtl_init<BKM, BN, BK, NL>(db, ldb, n0, N, lw);
   const int nk = K / BK;
 #pragma unroll
   for (int t = 0; t < NS - 1; ++t)
-    if (t < nk) {
-      dtl_issue<AKM, BM, BK, NW>(da, A, lda, t * BK, smem + t * BUF);
-      dtl_issue<BKM, BN, BK, NW>(db, B, ldb, t * BK, smem + t * BUF + A_BYTES);
+    if (t < nk && (!TURNS || turn == 1)) {     // (tile 0 comes from waves 4-7; tile 1 is even iteration 0's, from waves 0-3)
+      dtl_issue<AKM, BM, BK, NL>(da, A, lda, t * BK, smem + t * BUF, lw);
+      dtl_issue<BKM, BN, BK, NL>(db, B, ldb, t * BK, smem + t * BUF + A_BYTES, lw);
     }
   int stage = 0;               // ring slot of tile `it`
   int fill = NS - 1;           // ring slot the next issued tile goes to
@@ -460,9 +467,9 @@ __device__ __forceinline__ void gemm_dtl_body(const uint16_t* __restrict__ A, in
     else if (NS >= 3 && newer >= 1) { if (NS >= 4 && newer >= 2) RV_WAIT_VMCNT(LPT * 2); else RV_WAIT_VMCNT(LPT * 1); }
     else RV_WAIT_VMCNT(0);
     __syncthreads();           // everyone's part of tile `it` is in LDS; everyone left tile it-1
-    if (it + NS - 1 < nk) {
-      dtl_issue<AKM, BM, BK, NW>(da, A, lda, (it + NS - 1) * BK, smem + fill * BUF);
-      dtl_issue<BKM, BN, BK, NW>(db, B, ldb, (it + NS - 1) * BK, smem + fill * BUF + A_BYTES);
+    if (it + NS - 1 < nk && (!TURNS || turn == (it & 1))) {
+      dtl_issue<AKM, BM, BK, NL>(da, A, lda, (it + NS - 1) * BK, smem + fill * BUF, lw);
+      dtl_issue<BKM, BN, BK, NL>(db, B, ldb, (it + NS - 1) * BK, smem + fill * BUF + A_BYTES, lw);
     }
     const char* curA = smem + stage * BUF;
     const char* curB = curA + A_BYTES;
