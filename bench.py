@@ -453,11 +453,19 @@ def bench_gemm(args):
     def operand(r, c, std):
         t = torch.empty(r, c, dtype=torch.bfloat16, device="cuda")
         return {"normal": lambda: t.normal_(std=std), "zeros": t.zero_, "ones": lambda: t.fill_(1.0)}[args.operands]()
-    A = operand(K, M, 1.0) if akm else operand(M, K, 1.0)
-    B = operand(K, N, 0.02) if bkm else operand(N, K, 0.02)
-    out = torch.empty(M, N, dtype=torch.float32 if epi == kk.EPI_F32 else torch.bfloat16, device="cuda")
+    # --sets > 1: cycle through that many operand/result sets, so a launch does not find its
+    # operands in the last-level cache from the launch before
+    sets = [(operand(K, M, 1.0) if akm else operand(M, K, 1.0), operand(K, N, 0.02) if bkm else operand(N, K, 0.02),
+             torch.empty(M, N, dtype=torch.float32 if epi == kk.EPI_F32 else torch.bfloat16, device="cuda"))
+            for _ in range(max(args.sets, 1))]
     bias = torch.zeros(N, dtype=torch.bfloat16, device="cuda")
-    ms, _, _ = events_ms(lambda: kk.gemm_bf16(A, akm, B, bkm, M, N, K, epi, out, bias=bias), args.steps, args.warmup, args.reps)
+    turn = {"i": 0}
+
+    def one():
+        A, B, out = sets[turn["i"] % len(sets)]
+        turn["i"] += 1
+        kk.gemm_bf16(A, akm, B, bkm, M, N, K, epi, out, bias=bias)
+    ms, _, _ = events_ms(one, args.steps, args.warmup, args.reps)
     tf = 2.0 * M * N * K / (ms * 1e-3) / 1e12
     return {"metric": "bf16 matrix product TFLOP/s", "value": tf, "unit": "TFLOP/s", "ms_per_step": ms, "dtype": "bf16",
             "config": {"workload": "gemm: M=%d N=%d K=%d %s, operands %s" % (M, N, K, args.layout, args.operands)},
@@ -494,6 +502,7 @@ def main():
     ap.add_argument("--n", type=float, default=None)
     ap.add_argument("--shape", default="8192,8192,8192", help="gemm: M,N,K")
     ap.add_argument("--layout", default="dgrad", choices=["fwd", "dgrad", "wgrad"])
+    ap.add_argument("--sets", type=int, default=1, help="gemm: operand sets cycled through (more than the cache holds: cold operands)")
     ap.add_argument("--operands", default="normal", choices=["normal", "zeros", "ones"])
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--cold", action="store_true", help="stage workloads: time right after --warmup steps (no wait for the steady state)")

@@ -9,8 +9,8 @@
 //   dX       dx = dy W^T   : A = dy k-contiguous, B = W  k-contiguous (its rows are the n's)
 //   dW       dW = x^T dy   : A = x  k-major,      B = dy k-major      (contraction over tokens)
 //
-// Tiling: a workgroup of 4 or 8 waves owns a BM x BN tile and walks K in steps of BK (64 or
-// 32); a wave owns a block of 32x32 MFMA tiles (v_mfma_f32_32x32x16_bf16).  Operand tiles go
+// Tiling: a workgroup of 4 or 8 waves owns a BM x BN tile and walks K in steps of BK (32 or
+// 64); a wave owns a block of 32x32 MFMA tiles (v_mfma_f32_32x32x16_bf16).  Operand tiles go
 // global -> LDS directly (global_load_lds_dwordx4) through a ring of NS stages, unpadded, bank
 // conflicts removed by an XOR swizzle (see "direct-to-LDS pipeline" below);
 //   k-contiguous operands sit in LDS as [row][BK k], read as one 16-byte fragment per lane;
@@ -275,8 +275,11 @@ __device__ __forceinline__ void write_tile_staged(const f32x16 (&acc)[TM][TN], c
 // address a lane fetches.
 //   k-contiguous tile [rows][BK]: physical chunk = c ^ ((row / rows_per_256B) % chunks_per_row)
 //   k-major tile [BK][cols]     : physical chunk = c ^ ((k & 3) << 2)   (64-byte granules)
-// NS stages form a ring: the loads of tile t+NS-1 are issued right after the barrier that
-// opens tile t, so a tile has NS-1 k-steps of compute time to arrive.
+// NS stages form a ring.  Plain form (four-wave tiles): the loads of tile t+NS-1 are issued
+// right after the barrier that opens tile t.  Pipelined form (the eight-wave 256x256 tile): see
+// gemm_dtl_body - the products are bound by how fast operand tiles arrive, inside a stage step
+// even more than alone (with seven of eight MFMAs taken out the step is 3 % shorter, without
+// the loads 24 %), so that tile keeps three 32-deep tiles in flight instead of one 64-deep one.
 __host__ __device__ constexpr int dtl_tile_bytes(int rows, int bk) { return rows * bk * 2; }
 
 template <bool KM, int ROWS, int BK, int NW>
@@ -348,6 +351,14 @@ __device__ __forceinline__ bf16x8 dtl_frag(const char* lds, int row0, int kk) {
   }
 }
 
+// Direct-to-LDS load in the scalar-base form: wave-uniform 64-bit base in SGPRs, per-lane byte
+// offset in one VGPR (no per-load address arithmetic), LDS block = lb + IMM through M0.
+__device__ __forceinline__ void dtl_load_s(const void* base, unsigned off, int m0v) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(off), "s"(base), "s"(m0v)
+               : "memory", "m0");
+}
 // s_waitcnt vmcnt(n) only (expcnt, lgkmcnt left at "no wait"); n < 64
 #define RV_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 15) | (((n) >> 4) << 14) | 0x0F70)
 
@@ -423,12 +434,10 @@ __device__ __forceinline__ void gemm_dtl_body(const uint16_t* __restrict__ A, in
   constexpr int WM = BM / 2, WN = BN / (NW / 2), TM = WM / 32, TN = WN / 32, KSTEPS = BK / 16;
   constexpr int A_BYTES = dtl_tile_bytes(BM, BK), B_BYTES = dtl_tile_bytes(BN, BK);
   constexpr int BUF = A_BYTES + B_BYTES;
-  // With eight waves and a two-stage ring the waves take turns feeding it: in even k-iterations
-  // waves 0-3 issue ALL loads of the next tile and waves 4-7 go straight to their MFMAs, in odd
-  // ones the other way round.  Waves w and w+4 share a SIMD, so while one of them is held up
-  // handing its loads to the memory pipeline the other keeps the matrix core busy.
-  constexpr bool TURNS = NW == 8 && NS == 2;
-  constexpr int NL = TURNS ? 4 : NW;                                        // loader waves per tile
+  // The eight-wave 256x256 tile runs the pipelined ring below; the four-wave tiles keep the
+  // plain ring (loads of tile t+NS-1 right after the barrier that opens tile t).
+  constexpr bool PIPELINED = NW == 8 && BM == 256 && BN == 256;
+  constexpr int NL = NW;                                                    // loader waves per tile
   constexpr int LPT = Dtl<AKM, BM, BK, NL>::N + Dtl<BKM, BN, BK, NL>::N;   // loads per lane per tile
   static_assert(LPT * (NS - 2) < 64, "vmcnt range");
   char* smem = dtl_smem;
@@ -445,53 +454,69 @@ __device__ __forceinline__ void gemm_dtl_body(const uint16_t* __restrict__ A, in
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int lw = wave % NL;            // this wave's share of a tile's loads
-  const int turn = wave / NL;          // 0 or 1 with TURNS, else 0
+  const int lw = wave;                 // this wave's share of a tile's loads
   Dtl<AKM, BM, BK, NL> da;
   Dtl<BKM, BN, BK, NL> db;
   dtl_init<AKM, BM, BK, NL>(da, lda, m0, M, lw);
   dtl_init<BKM, BN, BK, NL>(db, ldb, n0, N, lw);
   const int nk = K / BK;
+  if constexpr (PIPELINED) {
+    // Ring of NS slots, the slot hand-over INSIDE a k-tile.  Before the last k-step of tile s
+    // (its fragments are already in registers) the workgroup meets once: tile s+1 has landed
+    // and nobody reads tile s's slot any more.  Behind that barrier the first fragments of tile
+    // s+1 are read and the loads of tile s+NS go into the slot just left, one behind every
+    // few MFMAs of the last k-step - so NS-1 tiles are in flight while one is being used, and
+    // the matrix core does not wait at a tile boundary.
+    constexpr int NA = Dtl<AKM, BM, BK, NL>::N, NB = Dtl<BKM, BN, BK, NL>::N, LPS = NA + NB;
+    constexpr int STRIDE = (TM * TN) / LPS;            // MFMAs per load in the last k-step
+    static_assert(STRIDE >= 1 && STRIDE * LPS == TM * TN, "loads are dealt out evenly behind the MFMAs of the last k-step");
+    static_assert((NS - 1) * LPS < 64, "vmcnt range");
+    unsigned oa[NA], ob[NB];               // per-lane byte offsets of this wave's loads inside a tile
 #pragma unroll
-  for (int t = 0; t < NS - 1; ++t)
-    if (t < nk && (!TURNS || turn == 1)) {     // (tile 0 comes from waves 4-7; tile 1 is even iteration 0's, from waves 0-3)
-      dtl_issue<AKM, BM, BK, NL>(da, A, lda, t * BK, smem + t * BUF, lw);
-      dtl_issue<BKM, BN, BK, NL>(db, B, ldb, t * BK, smem + t * BUF + A_BYTES, lw);
+    for (int i = 0; i < NA; ++i) oa[i] = (unsigned)da.off[i] * 2u;
+#pragma unroll
+    for (int i = 0; i < NB; ++i) ob[i] = (unsigned)db.off[i] * 2u;
+    auto baseA = [&](int t) { return AKM ? A + (int64_t)t * BK * lda : A + (int64_t)t * BK; };
+    auto baseB = [&](int t) { return BKM ? B + (int64_t)t * BK * ldb : B + (int64_t)t * BK; };
+    // wait until at most `tiles` of this wave's newest tile loads are still in flight
+    auto wait_tiles = [&](int tiles) {
+      if (NS >= 5 && tiles >= 4) RV_WAIT_VMCNT(4 * LPS);
+      else if (NS >= 5 && tiles == 3) RV_WAIT_VMCNT(3 * LPS);
+      else if (NS >= 4 && tiles >= 2) RV_WAIT_VMCNT(2 * LPS);
+      else if (NS >= 3 && tiles >= 1) RV_WAIT_VMCNT(1 * LPS);
+      else RV_WAIT_VMCNT(0);
+    };
+    static_assert(NS <= 5, "wait_tiles covers up to four tiles in flight behind the awaited one");
+    const int pre = nk < NS ? nk : NS;
+    for (int t = 0; t < pre; ++t) {
+      const int lb = __builtin_amdgcn_readfirstlane((int)(size_t)(smem + t * BUF) + lw * 1024);
+      const uint16_t* pa = baseA(t);
+      const uint16_t* pb = baseB(t);
+#pragma unroll
+      for (int q = 0; q < NA; ++q) dtl_load_s(pa, oa[q], lb + q * NL * 1024);
+#pragma unroll
+      for (int q = 0; q < NB; ++q) dtl_load_s(pb, ob[q], lb + A_BYTES + q * NL * 1024);
     }
-  int stage = 0;               // ring slot of tile `it`
-  int fill = NS - 1;           // ring slot the next issued tile goes to
-  for (int it = 0; it < nk; ++it) {
-    // tile `it` has landed once at most the loads of the newer tiles are outstanding
-    const int newer = nk - 1 - it;
-    if (NS >= 4 && newer >= NS - 2) RV_WAIT_VMCNT(LPT * (NS - 2));
-    else if (NS >= 3 && newer >= 1) { if (NS >= 4 && newer >= 2) RV_WAIT_VMCNT(LPT * 2); else RV_WAIT_VMCNT(LPT * 1); }
-    else RV_WAIT_VMCNT(0);
-    __syncthreads();           // everyone's part of tile `it` is in LDS; everyone left tile it-1
-    if (it + NS - 1 < nk && (!TURNS || turn == (it & 1))) {
-      dtl_issue<AKM, BM, BK, NL>(da, A, lda, (it + NS - 1) * BK, smem + fill * BUF, lw);
-      dtl_issue<BKM, BN, BK, NL>(db, B, ldb, (it + NS - 1) * BK, smem + fill * BUF + A_BYTES, lw);
-    }
-    const char* curA = smem + stage * BUF;
-    const char* curB = curA + A_BYTES;
+    wait_tiles(pre - 1);
+    __syncthreads();
     bf16x8 fa[2][TM], fb[2][TN];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) fa[0][i] = dtl_frag<AKM, BM, BK>(curA, wm0 + i * 32, 0);
+    for (int i = 0; i < TM; ++i) fa[0][i] = dtl_frag<AKM, BM, BK>(smem, wm0 + i * 32, 0);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) fb[0][j] = dtl_frag<BKM, BN, BK>(curB, wn0 + j * 32, 0);
+    for (int j = 0; j < TN; ++j) fb[0][j] = dtl_frag<BKM, BN, BK>(smem + A_BYTES, wn0 + j * 32, 0);
+    // k-steps 0 .. KSTEPS-2 of the tile in `cur` (fragments of k-step 0 already in fa[0], fb[0])
+    auto head_steps = [&](const char* curA, const char* curB) {
 #pragma unroll
-    for (int kk = 0; kk < KSTEPS; ++kk) {
-      if (kk + 1 < KSTEPS) {
+      for (int kk = 0; kk + 1 < KSTEPS; ++kk) {
 #pragma unroll
         for (int i = 0; i < TM; ++i) fa[(kk + 1) & 1][i] = dtl_frag<AKM, BM, BK>(curA, wm0 + i * 32, kk + 1);
 #pragma unroll
         for (int j = 0; j < TN; ++j) fb[(kk + 1) & 1][j] = dtl_frag<BKM, BN, BK>(curB, wn0 + j * 32, kk + 1);
-      }
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk & 1][j], fa[kk & 1][i], acc[i][j], 0, 0, 0);
-      if (kk + 1 < KSTEPS) {
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk & 1][j], fa[kk & 1][i], acc[i][j], 0, 0, 0);
         constexpr int NREAD = (AKM ? 2 : 1) * TM + (BKM ? 2 : 1) * TN;
         constexpr int NMFMA = TM * TN;
         constexpr int PER = NMFMA / NREAD > 0 ? NMFMA / NREAD : 1;
@@ -501,9 +526,120 @@ __device__ __forceinline__ void gemm_dtl_body(const uint16_t* __restrict__ A, in
           __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);
         }
       }
+    };
+    auto next_frags = [&](const char* nxtA) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i) fa[0][i] = dtl_frag<AKM, BM, BK>(nxtA, wm0 + i * 32, 0);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) fb[0][j] = dtl_frag<BKM, BN, BK>(nxtA + A_BYTES, wn0 + j * 32, 0);
+    };
+    static_assert((KSTEPS & 1) == 0, "the next tile's first fragments go to buffer 0");
+    constexpr int L = (KSTEPS - 1) & 1;      // the last k-step's fragments are in fa[L], fb[L]
+    int slot = 0;                            // ring slot of tile s
+    int s = 0;
+    for (; s + NS < nk; ++s) {               // passes that still have a tile s+NS to fetch
+      const char* curA = smem + slot * BUF;
+      const int nslot = slot + 1 == NS ? 0 : slot + 1;
+      head_steps(curA, curA + A_BYTES);
+      RV_WAIT_VMCNT((NS - 2) * LPS);         // tile s+1 (tiles s+2 .. s+NS-1 may still fly)
+      __syncthreads();                       // all of tile s+1 is in LDS; all fragment reads of tile s are done
+      next_frags(smem + nslot * BUF);
+      const int lb = __builtin_amdgcn_readfirstlane((int)(size_t)(smem + slot * BUF) + lw * 1024);
+      const uint16_t* pa = baseA(s + NS);
+      const uint16_t* pb = baseB(s + NS);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const int m = i * TN + j;
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[L][j], fa[L][i], acc[i][j], 0, 0, 0);
+          if (m % STRIDE == 0) {
+            const int q = m / STRIDE;
+            __builtin_amdgcn_sched_barrier(0);
+            if (q < NA) dtl_load_s(pa, oa[q], lb + q * NL * 1024);
+            else dtl_load_s(pb, ob[q - NA], lb + A_BYTES + (q - NA) * NL * 1024);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
+      slot = nslot;
     }
-    stage = stage + 1 == NS ? 0 : stage + 1;
-    fill = fill + 1 == NS ? 0 : fill + 1;
+    for (; s + 1 < nk; ++s) {                // the last NS-1 hand-overs: nothing left to fetch
+      const char* curA = smem + slot * BUF;
+      const int nslot = slot + 1 == NS ? 0 : slot + 1;
+      head_steps(curA, curA + A_BYTES);
+      wait_tiles(nk - 2 - s);                // tiles s+2 .. nk-1 may still fly
+      __syncthreads();
+      next_frags(smem + nslot * BUF);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[L][j], fa[L][i], acc[i][j], 0, 0, 0);
+      slot = nslot;
+    }
+    {
+      const char* curA = smem + slot * BUF;
+      head_steps(curA, curA + A_BYTES);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[L][j], fa[L][i], acc[i][j], 0, 0, 0);
+    }
+  } else {
+#pragma unroll
+    for (int t = 0; t < NS - 1; ++t)
+      if (t < nk) {
+        dtl_issue<AKM, BM, BK, NL>(da, A, lda, t * BK, smem + t * BUF, lw);
+        dtl_issue<BKM, BN, BK, NL>(db, B, ldb, t * BK, smem + t * BUF + A_BYTES, lw);
+      }
+    int stage = 0;               // ring slot of tile `it`
+    int fill = NS - 1;           // ring slot the next issued tile goes to
+    for (int it = 0; it < nk; ++it) {
+      // tile `it` has landed once at most the loads of the newer tiles are outstanding
+      const int newer = nk - 1 - it;
+      if (NS >= 4 && newer >= NS - 2) RV_WAIT_VMCNT(LPT * (NS - 2));
+      else if (NS >= 3 && newer >= 1) { if (NS >= 4 && newer >= 2) RV_WAIT_VMCNT(LPT * 2); else RV_WAIT_VMCNT(LPT * 1); }
+      else RV_WAIT_VMCNT(0);
+      __syncthreads();           // everyone's part of tile `it` is in LDS; everyone left tile it-1
+      if (it + NS - 1 < nk) {
+        dtl_issue<AKM, BM, BK, NL>(da, A, lda, (it + NS - 1) * BK, smem + fill * BUF, lw);
+        dtl_issue<BKM, BN, BK, NL>(db, B, ldb, (it + NS - 1) * BK, smem + fill * BUF + A_BYTES, lw);
+      }
+      const char* curA = smem + stage * BUF;
+      const char* curB = curA + A_BYTES;
+      bf16x8 fa[2][TM], fb[2][TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) fa[0][i] = dtl_frag<AKM, BM, BK>(curA, wm0 + i * 32, 0);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) fb[0][j] = dtl_frag<BKM, BN, BK>(curB, wn0 + j * 32, 0);
+#pragma unroll
+      for (int kk = 0; kk < KSTEPS; ++kk) {
+        if (kk + 1 < KSTEPS) {
+#pragma unroll
+          for (int i = 0; i < TM; ++i) fa[(kk + 1) & 1][i] = dtl_frag<AKM, BM, BK>(curA, wm0 + i * 32, kk + 1);
+#pragma unroll
+          for (int j = 0; j < TN; ++j) fb[(kk + 1) & 1][j] = dtl_frag<BKM, BN, BK>(curB, wn0 + j * 32, kk + 1);
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[kk & 1][j], fa[kk & 1][i], acc[i][j], 0, 0, 0);
+        if (kk + 1 < KSTEPS) {
+          constexpr int NREAD = (AKM ? 2 : 1) * TM + (BKM ? 2 : 1) * TN;
+          constexpr int NMFMA = TM * TN;
+          constexpr int PER = NMFMA / NREAD > 0 ? NMFMA / NREAD : 1;
+#pragma unroll
+          for (int g = 0; g < NREAD; ++g) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);
+          }
+        }
+      }
+      stage = stage + 1 == NS ? 0 : stage + 1;
+      fill = fill + 1 == NS ? 0 : fill + 1;
+    }
   }
   if constexpr (staged_epi(EPI)) {
     write_tile_staged<BM, BN, 64 * NW, TM, TN, EPI>(acc, e, m0, n0, wm0, wn0, M, N, smem);
@@ -552,9 +688,10 @@ __global__ __launch_bounds__(64 * NW, WPE) void gemm_dtl_grouped_wgrad_kernel(Gr
     if (k < ga.count && v >= ga.p[k].first_tile) pi = k;
   const GroupedProblem& q = ga.p[pi];
   const int local = v - q.first_tile;
-  const int band = local / (2 * q.tiles_n), first_row = band * 2;
-  const int rows = q.tiles_m - first_row < 2 ? q.tiles_m - first_row : 2;
-  const int in = local - band * 2 * q.tiles_n;
+  constexpr int GB = 2;
+  const int band = local / (GB * q.tiles_n), first_row = band * GB;
+  const int rows = q.tiles_m - first_row < GB ? q.tiles_m - first_row : GB;
+  const int in = local - band * GB * q.tiles_n;
   Epi e{q.out, q.ldo, q.upd_ver, nullptr, nullptr, 0, nullptr, q.upd_w, q.eta, nullptr};
   gemm_dtl_body<BM, BN, BK, NS, NW, true, true, EPI_F32_UPD>(q.A, q.lda, q.B, q.ldb, q.M, q.N, q.K, first_row + in % rows,
                                                       in / rows, e);
@@ -582,8 +719,9 @@ rv_status launch_dtl(const rv_gemm_args& g, hipStream_t st) {
 }
 
 // Tile choice (codes: 5256, 2256, 2192, 2128).
-//   5256  256x256, eight waves of 128x64, BK 64, two stages, one workgroup per CU: lowest
-//         LDS traffic per MFMA, two waves per SIMD cover each other's barrier stalls;
+//   5256  256x256, eight waves of 128x64, BK 32, ring of four slots run in the pipelined form
+//         (three tiles in flight, loads dealt out behind the MFMAs), one workgroup per CU:
+//         lowest LDS traffic per MFMA, two waves per SIMD cover each other's stalls;
 //   2192  128x256, four waves of 64x128, BK 32, three stages, two workgroups per CU;
 //   2128  128x128, four waves of 64x64, BK 64, two stages, two workgroups per CU: fills the
 //         chip on small outputs.
@@ -610,7 +748,7 @@ rv_status pick_tile(const rv_gemm_args& g, hipStream_t st) {
   if (tile == 2256) return launch_dtl<256, 256, 32, 4, 4, 1, AKM, BKM, EPI>(g, st);
   if (tile == 2192) return launch_dtl<128, 256, 32, 3, 4, 2, AKM, BKM, EPI>(g, st);
   if (tile == 2128) return launch_dtl<128, 128, 64, 2, 4, 2, AKM, BKM, EPI>(g, st);
-  if (tile == 5256) return launch_dtl<256, 256, 64, 2, 8, 2, AKM, BKM, EPI>(g, st);
+  if (tile == 5256) return launch_dtl<256, 256, 32, 4, 8, 2, AKM, BKM, EPI>(g, st);
   return RV_E_INVAL;
 }
 
@@ -700,7 +838,7 @@ rv_status rv_gemm_wgrad_grouped(const rv_gemm_args* gs, int count, hipStream_t s
   // 256x256 tiles, eight waves (measured against 128x128 and 128x256 tiles, alone and inside the
   // stage step of configs 2, 3 and 5: fewest LDS bytes per MFMA, so it takes the least CU time
   // from the kernels that run beside it, and the step is 3-4 % shorter)
-  return launch_grouped<256, 256, 64, 2, 8>(gs, count, st);
+  return launch_grouped<256, 256, 32, 4, 8>(gs, count, st);
 }
 
 extern "C" rv_status rv_k_gemm_bf16(const void* A, int64_t lda, int a_kmajor, const void* B, int64_t ldb,
