@@ -150,9 +150,11 @@ __global__ __launch_bounds__(64 * kBwdWaves, NV <= 2 ? 6 : 1) void ln_bwd_kernel
         const int c = cbase + 256 * i;
         xh[q][i] = 0.f; rs[q][i] = 0.f; dyr[q][i] = u32x2{0u, 0u};
         if (valid && c < d) {
-          xh[q][i] = *reinterpret_cast<const f32x4*>(x + (int64_t)row * d + c);
-          rs[q][i] = *reinterpret_cast<const f32x4*>(dres + (int64_t)row * d + c);
-          dyr[q][i] = *reinterpret_cast<const u32x2*>(dy + (int64_t)row * d + c);
+          // read once, written once: the non-temporal hint keeps these rows from pushing the
+          // operand panels of the matrix products on the other streams out of L2
+          xh[q][i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(x + (int64_t)row * d + c));
+          rs[q][i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(dres + (int64_t)row * d + c));
+          dyr[q][i] = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(dy + (int64_t)row * d + c));
         }
       }
     }
@@ -189,8 +191,8 @@ __global__ __launch_bounds__(64 * kBwdWaves, NV <= 2 ? 6 : 1) void ln_bwd_kernel
             const f32x4 dyv = bf16x4_to_f32(dyr[q][i]);
             const f32x4 dxh = dyv * gam[i];
             const f32x4 o = (dxh - c1 - xh[q][i] * c2) * r[q] + rs[q][i];
-            *reinterpret_cast<f32x4*>(dx + (int64_t)row * d + c) = o;
-            if (dx_bf16) *reinterpret_cast<u32x2*>(dx_bf16 + (int64_t)row * d + c) = f32_to_bf16x4(o);
+            __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(dx + (int64_t)row * d + c));
+            if (dx_bf16) __builtin_nontemporal_store(f32_to_bf16x4(o), reinterpret_cast<u32x2*>(dx_bf16 + (int64_t)row * d + c));
             ag[i] += dyv * xh[q][i];
             ab[i] += dyv;
             ax[i] += o;
