@@ -79,6 +79,31 @@ def test_weight_gradient_product(M, N, K, tile):
     close(host64(o), x64.T @ dy64, 1e-5, "gemm", group=GROUP[1e-5])
 
 
+@pytest.mark.parametrize("K", [64, 128, 192, 256, 320, 384, 448, 576])
+def test_ring_depths_of_the_256_tile(K):
+    """The 256x256 tile walks K through a four-slot ring of 32-deep tiles (K/32 = 2 .. 18 tiles:
+    fewer tiles than slots, exactly as many, one more, and a few turns of the ring), each layout,
+    on a ragged output (two tile rows, two tile columns, the last of each partly filled)."""
+    from paper_2401_01728_amd import kernels as k
+    M, N = 328, 456
+    x, x64 = bf16_normal(11, 0, (M, K)); w, w64 = bf16_normal(11, 1, (K, N), std=0.05)
+    b, b64 = bf16_normal(11, 2, (N,), std=0.5)
+    o = _out((M, N), torch.bfloat16)
+    k.gemm_bf16(x, 0, w, 1, M, N, K, k.EPI_BF16_BIAS, o, bias=b, tile=5256)            # forward layout
+    close(host64(o), x64 @ w64 + b64, 4e-3, "gemm", group=GROUP[4e-3])
+    wt, wt64 = bf16_normal(11, 3, (N, K), std=0.05)
+    o = _out((M, N), torch.bfloat16)
+    k.gemm_bf16(x, 0, wt, 0, M, N, K, k.EPI_BF16, o, tile=5256)                         # input-gradient layout
+    close(host64(o), x64 @ wt64.T, 4e-3, "gemm", group=GROUP[4e-3])
+    xt, xt64 = bf16_normal(11, 4, (K, M)); dy, dy64 = bf16_normal(11, 5, (K, N), std=1e-2)
+    o32 = _out((M, N), torch.float32)
+    k.gemm_bf16(xt, 1, dy, 1, M, N, K, k.EPI_F32, o32, tile=5256)                       # weight-gradient layout
+    close(host64(o32), xt64.T @ dy64, 1e-5, "gemm", group=GROUP[1e-5])
+    g32 = _out((M, N), torch.float32)
+    k.gemm_wgrad_grouped([xt], [dy], [g32])
+    assert torch.equal(g32, o32)
+
+
 def test_strided_operands_and_rejects():
     """Operands that are column blocks of wider matrices (pitch > width), as q|k|v are."""
     from paper_2401_01728_amd import kernels as k
