@@ -78,20 +78,24 @@ enum { EPI_BF16 = RV_EPI_BF16, EPI_BF16_BIAS = RV_EPI_BF16_BIAS, EPI_F32_BIAS_RE
        // stand-alone update kernel does it) and out2 bf16 = the new w
        EPI_F32_UPD = 7 };
 
+constexpr bool epi_has_bias(int epi) {
+  return epi == EPI_BF16_BIAS || epi == EPI_F32_BIAS_RESID || epi == EPI_BF16_BIAS_GELU || epi == EPI_F32_BIAS_RESID_BF16;
+}
+constexpr bool epi_has_resid(int epi) { return epi == EPI_F32_BIAS_RESID || epi == EPI_F32_BIAS_RESID_BF16; }
+
+__device__ __forceinline__ void add_bias4(f32x4& a, u32x2 b) {
+  a.x += __uint_as_float(b.x << 16); a.y += __uint_as_float(b.x & 0xFFFF0000u);
+  a.z += __uint_as_float(b.y << 16); a.w += __uint_as_float(b.y & 0xFFFF0000u);
+}
+
+// four consecutive columns n..n+3 of row m; b = their bias, r = their residual (already loaded)
 template <int EPI>
-__device__ __forceinline__ void epilogue4(const Epi& e, int m, int n, f32x4 a) {
-  // four consecutive columns n..n+3 of row m
-  if (EPI == EPI_BF16_BIAS || EPI == EPI_F32_BIAS_RESID || EPI == EPI_BF16_BIAS_GELU ||
-      EPI == EPI_F32_BIAS_RESID_BF16) {
-    u32x2 b = *reinterpret_cast<const u32x2*>(e.bias + n);
-    a.x += __uint_as_float(b.x << 16); a.y += __uint_as_float(b.x & 0xFFFF0000u);
-    a.z += __uint_as_float(b.y << 16); a.w += __uint_as_float(b.y & 0xFFFF0000u);
-  }
+__device__ __forceinline__ void epilogue4(const Epi& e, int m, int n, f32x4 a, u32x2 b, f32x4 r) {
+  if (epi_has_bias(EPI)) add_bias4(a, b);
   if (EPI == EPI_BF16 || EPI == EPI_BF16_BIAS) {
     u32x2 o; o.x = rv_pack_bf16x2(a.x, a.y); o.y = rv_pack_bf16x2(a.z, a.w);
     *reinterpret_cast<u32x2*>((uint16_t*)e.out + (int64_t)m * e.ldo + n) = o;
-  } else if (EPI == EPI_F32_BIAS_RESID || EPI == EPI_F32_BIAS_RESID_BF16) {
-    f32x4 r = *reinterpret_cast<const f32x4*>(e.resid + (int64_t)m * e.ldr + n);
+  } else if (epi_has_resid(EPI)) {
     a += r;
     *reinterpret_cast<f32x4*>((float*)e.out + (int64_t)m * e.ldo + n) = a;
     if (EPI == EPI_F32_BIAS_RESID_BF16) {
@@ -121,22 +125,51 @@ __device__ __forceinline__ void epilogue4(const Epi& e, int m, int n, f32x4 a) {
 
 // lane holds row m = l%32 of the wave tile and, per group rg of 4 registers,
 // columns 8*rg + 4*(l/32) .. +3
+// What an epilogue reads (bias, residual) is requested for a whole batch of column groups, at
+// addresses clamped into the matrix, before the first result is formed: a batch costs one
+// memory round trip, not one per group of four columns.
 template <int TM, int TN, int EPI>
 __device__ __forceinline__ void write_tile(const f32x16 (&acc)[TM][TN], const Epi& e, int mw, int nw, int M, int N) {
   const int l = threadIdx.x & 63;
+  constexpr int JB = TN > 2 ? 2 : TN;          // tile columns per batch of residual loads
+  u32x2 bias4[TN][4];
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+#pragma unroll
+    for (int rg = 0; rg < 4; ++rg) {
+      bias4[j][rg] = u32x2{0u, 0u};
+      if (epi_has_bias(EPI)) {
+        const int n = nw + j * 32 + 8 * rg + 4 * (l >> 5);
+        bias4[j][rg] = *reinterpret_cast<const u32x2*>(e.bias + (n < N ? n : N - 4));
+      }
+    }
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
     const int m = mw + i * 32 + (l & 31);
-    if (m >= M) continue;
+    const int mc = m < M ? m : M - 1;
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
+    for (int j0 = 0; j0 < TN; j0 += JB) {
+      f32x4 res[JB][4];
 #pragma unroll
-      for (int rg = 0; rg < 4; ++rg) {
-        const int n = nw + j * 32 + 8 * rg + 4 * (l >> 5);
-        if (n >= N) continue;
-        f32x4 a = {acc[i][j][4 * rg], acc[i][j][4 * rg + 1], acc[i][j][4 * rg + 2], acc[i][j][4 * rg + 3]};
-        epilogue4<EPI>(e, m, n, a);
-      }
+      for (int jj = 0; jj < JB; ++jj)
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {
+          res[jj][rg] = f32x4{0.f, 0.f, 0.f, 0.f};
+          if (epi_has_resid(EPI)) {
+            const int n = nw + (j0 + jj) * 32 + 8 * rg + 4 * (l >> 5);
+            res[jj][rg] = *reinterpret_cast<const f32x4*>(e.resid + (int64_t)mc * e.ldr + (n < N ? n : N - 4));
+          }
+        }
+#pragma unroll
+      for (int jj = 0; jj < JB; ++jj)
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {
+          const int j = j0 + jj;
+          const int n = nw + j * 32 + 8 * rg + 4 * (l >> 5);
+          if (m >= M || n >= N) continue;
+          f32x4 a = {acc[i][j][4 * rg], acc[i][j][4 * rg + 1], acc[i][j][4 * rg + 2], acc[i][j][4 * rg + 3]};
+          epilogue4<EPI>(e, m, n, a, bias4[j][rg], res[jj][rg]);
+        }
     }
   }
 }
@@ -183,13 +216,25 @@ __device__ __forceinline__ void write_tile_staged(const f32x16 (&acc)[TM][TN], c
   if (EPI == EPI_BF16_DGELU) {
     // the pre-activation tile comes in the way the result goes out: whole rows, 16 bytes per
     // lane, through the image; a lane then finds its own four values where it will put the result
-    constexpr int CPR = BN / 8;
-    for (int idx = threadIdx.x; idx < BM * CPR; idx += NT) {
-      const int row = idx / CPR, c = idx % CPR;
-      const int gm = m0 + row, gn = n0 + c * 8;
-      if (gm < M && gn < N)
-        *reinterpret_cast<u32x4*>(smem + row * PITCH + c * 16) =
-            *reinterpret_cast<const u32x4*>(e.zin + (int64_t)gm * e.ldo + gn);
+    // (eight loads per lane in flight before the first is parked: two memory round trips per
+    // tile instead of one per 16-byte piece)
+    constexpr int CPR = BN / 8, PIECES = BM * CPR / NT, BATCH = NT >= 512 ? 8 : 4;
+    static_assert(BM * CPR % NT == 0 && PIECES % BATCH == 0, "whole batches");
+#pragma unroll 1
+    for (int p0 = 0; p0 < PIECES; p0 += BATCH) {
+      u32x4 v[BATCH];
+#pragma unroll
+      for (int u = 0; u < BATCH; ++u) {
+        const int idx = threadIdx.x + (p0 + u) * NT, row = idx / CPR, c = idx % CPR;
+        const int gm = m0 + row, gn = n0 + c * 8;
+        v[u] = u32x4{0u, 0u, 0u, 0u};
+        if (gm < M && gn < N) v[u] = *reinterpret_cast<const u32x4*>(e.zin + (int64_t)gm * e.ldo + gn);
+      }
+#pragma unroll
+      for (int u = 0; u < BATCH; ++u) {
+        const int idx = threadIdx.x + (p0 + u) * NT, row = idx / CPR, c = idx % CPR;
+        *reinterpret_cast<u32x4*>(smem + row * PITCH + c * 16) = v[u];
+      }
     }
     __syncthreads();
   }
@@ -204,6 +249,17 @@ __device__ __forceinline__ void write_tile_staged(const f32x16 (&acc)[TM][TN], c
 #pragma unroll
       for (int rg = 0; rg < 4; ++rg) cs[j][rg] = 0.f;
   }
+  u32x2 bias4[TN][4];                            // this lane's bias values, loaded once
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+#pragma unroll
+    for (int rg = 0; rg < 4; ++rg) {
+      bias4[j][rg] = u32x2{0u, 0u};
+      if (EPI == EPI_BF16_BIAS || EPI == EPI_BF16_BIAS_GELU) {
+        const int gn = n0 + wn0 + j * 32 + 8 * rg + 4 * (l >> 5);
+        bias4[j][rg] = *reinterpret_cast<const u32x2*>(e.bias + (gn < N ? gn : N - 4));
+      }
+    }
 #pragma unroll
   for (int pass = 0; pass < PASSES; ++pass) {
 #pragma unroll
@@ -217,11 +273,7 @@ __device__ __forceinline__ void write_tile_staged(const f32x16 (&acc)[TM][TN], c
           const int gm = m0 + ml, gn = n0 + nl;
           f32x4 a = {acc[i][j][4 * rg], acc[i][j][4 * rg + 1], acc[i][j][4 * rg + 2], acc[i][j][4 * rg + 3]};
           if (EPI == EPI_BF16_BIAS || EPI == EPI_BF16_BIAS_GELU) {
-            if (gn < N) {
-              u32x2 b = *reinterpret_cast<const u32x2*>(e.bias + gn);
-              a.x += __uint_as_float(b.x << 16); a.y += __uint_as_float(b.x & 0xFFFF0000u);
-              a.z += __uint_as_float(b.y << 16); a.w += __uint_as_float(b.y & 0xFFFF0000u);
-            }
+            add_bias4(a, bias4[j][rg]);
             if (pass == 1) { a.x = gelu_f(a.x); a.y = gelu_f(a.y); a.z = gelu_f(a.z); a.w = gelu_f(a.w); }
           }
           if (EPI == EPI_BF16_DGELU) {
@@ -255,13 +307,22 @@ __device__ __forceinline__ void write_tile_staged(const f32x16 (&acc)[TM][TN], c
         if (n0 + c < N) e.colpart[(int64_t)(m0 / BM) * e.ldo + n0 + c] = red[c] + red[BN + c];
     }
     uint16_t* dst = (uint16_t*)(pass == 0 ? e.out : e.out2);
-    constexpr int CPR = BN / 8;
-    for (int idx = threadIdx.x; idx < BM * CPR; idx += NT) {
-      const int row = idx / CPR, c = idx % CPR;
-      const int gm = m0 + row, gn = n0 + c * 8;
-      if (gm < M && gn < N)
-        *reinterpret_cast<u32x4*>(dst + (int64_t)gm * e.ldo + gn) =
-            *reinterpret_cast<const u32x4*>(smem + row * PITCH + c * 16);
+    constexpr int CPR = BN / 8, PIECES = BM * CPR / NT, BATCH = NT >= 512 ? 8 : 4;
+    static_assert(BM * CPR % NT == 0 && PIECES % BATCH == 0, "whole batches");
+#pragma unroll 1
+    for (int p0 = 0; p0 < PIECES; p0 += BATCH) {
+      u32x4 v[BATCH];
+#pragma unroll
+      for (int u = 0; u < BATCH; ++u) {
+        const int idx = threadIdx.x + (p0 + u) * NT, row = idx / CPR, c = idx % CPR;
+        v[u] = *reinterpret_cast<const u32x4*>(smem + row * PITCH + c * 16);
+      }
+#pragma unroll
+      for (int u = 0; u < BATCH; ++u) {
+        const int idx = threadIdx.x + (p0 + u) * NT, row = idx / CPR, c = idx % CPR;
+        const int gm = m0 + row, gn = n0 + c * 8;
+        if (gm < M && gn < N) *reinterpret_cast<u32x4*>(dst + (int64_t)gm * e.ldo + gn) = v[u];
+      }
     }
     if (pass + 1 < PASSES) __syncthreads();
   }

@@ -58,16 +58,18 @@ __global__ __launch_bounds__(kThreads, NV <= 8 ? 6 : 1) void ln_fwd_kernel(const
   float s = 0.f;
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
+    // every lane loads (columns past the row's end re-read its last four and are zeroed): no
+    // branch around a load, so all NV of them are in flight together
+    const int c = l * 4 + 256 * i, cc = c < d ? c : d - 4;
+    if (IN_BF16) v[i] = bf16x4_to_f32(*reinterpret_cast<const u32x2*>((const uint16_t*)xin + (int64_t)row * d + cc));
+    else v[i] = *reinterpret_cast<const f32x4*>((const float*)xin + (int64_t)row * d + cc);
+    if (c >= d) v[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
     const int c = l * 4 + 256 * i;
-    if (c < d) {
-      if (IN_BF16) {
-        v[i] = bf16x4_to_f32(*reinterpret_cast<const u32x2*>((const uint16_t*)xin + (int64_t)row * d + c));
-        *reinterpret_cast<f32x4*>(xcopy + (int64_t)row * d + c) = v[i];
-      } else {
-        v[i] = *reinterpret_cast<const f32x4*>((const float*)xin + (int64_t)row * d + c);
-      }
-      s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
-    }
+    if (IN_BF16 && c < d) *reinterpret_cast<f32x4*>(xcopy + (int64_t)row * d + c) = v[i];
+    s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
   }
   const float mu = wave_sum(s) / (float)d;
   float q = 0.f;
@@ -83,13 +85,11 @@ __global__ __launch_bounds__(kThreads, NV <= 8 ? 6 : 1) void ln_fwd_kernel(const
   if (l == 0) { mean[row] = mu; rstd[row] = r; }
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
-    const int c = l * 4 + 256 * i;
-    if (c < d) {
-      f32x4 g = bf16x4_to_f32(*reinterpret_cast<const u32x2*>(gamma + c));
-      f32x4 b = bf16x4_to_f32(*reinterpret_cast<const u32x2*>(beta + c));
-      f32x4 o = (v[i] - mu) * r * g + b;
-      *reinterpret_cast<u32x2*>(y + (int64_t)row * d + c) = f32_to_bf16x4(o);
-    }
+    const int c = l * 4 + 256 * i, cc = c < d ? c : d - 4;
+    const f32x4 g = bf16x4_to_f32(*reinterpret_cast<const u32x2*>(gamma + cc));
+    const f32x4 b = bf16x4_to_f32(*reinterpret_cast<const u32x2*>(beta + cc));
+    const f32x4 o = (v[i] - mu) * r * g + b;
+    if (c < d) *reinterpret_cast<u32x2*>(y + (int64_t)row * d + c) = f32_to_bf16x4(o);
   }
 }
 
@@ -131,7 +131,8 @@ __global__ __launch_bounds__(64 * kBwdWaves, NV <= 2 ? 6 : 1) void ln_bwd_kernel
   for (int i = 0; i < NV; ++i) {
     ag[i] = 0.f; ab[i] = 0.f; ax[i] = 0.f; gam[i] = 0.f;
     const int c = cbase + 256 * i;
-    if (c < d) gam[i] = bf16x4_to_f32(*reinterpret_cast<const u32x2*>(gamma + c));
+    gam[i] = bf16x4_to_f32(*reinterpret_cast<const u32x2*>(gamma + (c < d ? c : d - 4)));
+    if (c >= d) gam[i] = f32x4{0.f, 0.f, 0.f, 0.f};
   }
 #pragma unroll 1
   for (int k = 0; k < kRowsPerBlock / RF; ++k) {
@@ -222,13 +223,19 @@ __global__ __launch_bounds__(kThreads) void widen_colsum_kernel(const uint16_t* 
   if (c >= d) return;
   const int r0 = blockIdx.y * kWidenRows;
   f32x4 acc = 0.f;
-#pragma unroll 8
-  for (int r = r0; r < r0 + kWidenRows; ++r) {
-    if (r < T) {
-      const f32x4 v = bf16x4_to_f32(*reinterpret_cast<const u32x2*>(a + (int64_t)r * d + c));
-      *reinterpret_cast<f32x4*>(o + (int64_t)r * d + c) = v;
-      acc += v;
-    }
+  static_assert(kWidenRows % 8 == 0, "batches of eight rows");
+#pragma unroll 1
+  for (int rb = r0; rb < r0 + kWidenRows; rb += 8) {
+    u32x2 raw[8];                               // eight rows requested before the first is used
+#pragma unroll
+    for (int u = 0; u < 8; ++u) raw[u] = *reinterpret_cast<const u32x2*>(a + (int64_t)(rb + u < T ? rb + u : T - 1) * d + c);
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (rb + u < T) {
+        const f32x4 v = bf16x4_to_f32(raw[u]);
+        *reinterpret_cast<f32x4*>(o + (int64_t)(rb + u) * d + c) = v;
+        acc += v;
+      }
   }
   *reinterpret_cast<f32x4*>(part + (int64_t)blockIdx.y * d + c) = acc;
 }
@@ -248,18 +255,23 @@ __global__ __launch_bounds__(kThreads) void reduce_rows_kernel(ReduceJobs jobs, 
   const float* __restrict__ src = jobs.src[blockIdx.y];
   const int cl = threadIdx.x & 31, rl = threadIdx.x >> 5;
   const int c = blockIdx.x * 32 + cl;
-  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};   // eight loads in flight per lane
   if (c < N) {
     int r = rl;
-    for (; r + 24 < R; r += 32) {
-      s0 += src[(int64_t)r * pitch + c];
-      s1 += src[(int64_t)(r + 8) * pitch + c];
-      s2 += src[(int64_t)(r + 16) * pitch + c];
-      s3 += src[(int64_t)(r + 24) * pitch + c];
+    for (; r + 56 < R; r += 64) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s[u] += src[(int64_t)(r + 8 * u) * pitch + c];
     }
-    for (; r < R; r += 8) s0 += src[(int64_t)r * pitch + c];
+    float t[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {       // the last, partial round: rows past the end re-read row R-1 and count as zero
+      const int rr = r + 8 * u;
+      t[u] = src[(int64_t)(rr < R ? rr : R - 1) * pitch + c];
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s[u] += r + 8 * u < R ? t[u] : 0.f;
   }
-  red[rl][cl] = (s0 + s1) + (s2 + s3);
+  red[rl][cl] = ((s[0] + s[1]) + (s[2] + s[3])) + ((s[4] + s[5]) + (s[6] + s[7]));
   __syncthreads();
   if (rl == 0 && c < N) {
     float t = red[0][cl];
