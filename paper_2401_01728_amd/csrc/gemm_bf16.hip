@@ -59,6 +59,9 @@ __device__ __forceinline__ float dgelu_f(float z) {
   return __fmaf_rn(z * 0.3989422804014327f, e, cdf);
 }
 
+#ifndef RV_RESID_LDS
+#define RV_RESID_LDS 1
+#endif
 struct Epi {
   void* out; int64_t ldo;
   void* out2;
@@ -118,7 +121,7 @@ __device__ __forceinline__ void epilogue4(const Epi& e, int m, int n, f32x4 a, u
   } else if (EPI == EPI_F32) {
     *reinterpret_cast<f32x4*>((float*)e.out + (int64_t)m * e.ldo + n) = a;
   } else if (EPI == EPI_F32_UPD) {
-    // (no update asked for: the gradient tile alone; the update path is update_tile_staged)
+    // (no update asked for: the gradient tile alone; the update path is f32_tile_through_lds)
     *reinterpret_cast<f32x4*>((float*)e.out + (int64_t)m * e.ldo + n) = a;
   }
 }
@@ -434,21 +437,43 @@ extern __shared__ __align__(1024) char dtl_smem[];
 // 32 rows over the banks.
 __host__ __device__ constexpr int upd_image_bytes(int bm, int bn) { return (bm / 2) * (bn * 4 + 16); }
 
-template <int BM, int BN, int NW, int TM, int TN>
-__device__ __forceinline__ void update_tile_staged(const f32x16 (&acc)[TM][TN], const Epi& e, int m0, int n0,
-                                                   int wm0, int wn0, int M, int N, char* smem) {
+// MODE 0: the update above (source and fp32 result = e.upd_w, bf16 result = e.out2, the gradient itself to e.out
+//         on request).  MODE 1: out = acc + bias + residual (source = e.resid, fp32 result = e.out, and with
+//         BF16OUT its rounding to e.out2) - the same staging: at 4-byte results per lane-quad the direct form costs
+//         more L2 requests than a short product's whole main loop.
+// The results go back into the LDS rows they came from and leave the way the rows came in: whole rows, 16 bytes
+// per lane, one 128-byte line per 8 lanes, instead of 32-byte pieces of 32 different rows per store instruction.
+template <int BM, int BN, int NW, int TM, int TN, int MODE, bool BF16OUT>
+__device__ __forceinline__ void f32_tile_through_lds(const f32x16 (&acc)[TM][TN], const Epi& e, int m0, int n0,
+                                                     int wm0, int wn0, int M, int N, char* smem) {
   static_assert(BN == 256, "one direct-to-LDS instruction moves one 256-column fp32 row");
-  constexpr int HALF = BM / 2, PITCH = BN * 4 + 16;
+  constexpr int HALF = BM / 2, PITCH = BN * 4 + 16, RPW = HALF / NW;   // rows per wave in the row-wise phases
+  static_assert(HALF % NW == 0 && RPW % 8 == 0, "row batches of eight");
   const int wave = threadIdx.x >> 6, l = threadIdx.x & 63;
+  const float* srcm = MODE == 0 ? e.upd_w : e.resid;
+  const int64_t lds_src = MODE == 0 ? e.ldo : e.ldr;
+  float* dst32 = MODE == 0 ? e.upd_w : (float*)e.out;
+  u32x2 bias4[TN][4];
+#pragma unroll
+  for (int j = 0; j < TN; ++j)
+#pragma unroll
+    for (int rg = 0; rg < 4; ++rg) {
+      bias4[j][rg] = u32x2{0u, 0u};
+      if (MODE == 1) {
+        const int n = n0 + wn0 + j * 32 + 8 * rg + 4 * (l >> 5);
+        bias4[j][rg] = *reinterpret_cast<const u32x2*>(e.bias + (n < N ? n : N - 4));
+      }
+    }
+  int gn = n0 + l * 4;
+  const bool col_ok = gn < N;
+  gn = col_ok ? gn : N - 4;                    // ragged tiles fetch valid memory and ignore it below
 #pragma unroll 1
   for (int h = 0; h < 2; ++h) {
     __syncthreads();   // LDS is free: the operand ring (h = 0) or the other half's rows (h = 1)
-    int gn = n0 + l * 4;
-    gn = gn < N ? gn : N - 4;                  // ragged tiles fetch valid memory and ignore it below
     for (int r = wave; r < HALF; r += NW) {
       int gm = m0 + h * HALF + r;
       gm = gm < M ? gm : M - 1;
-      const float* src = e.upd_w + (int64_t)gm * e.ldo + gn;
+      const float* src = srcm + (int64_t)gm * lds_src + gn;
       const int m0v = __builtin_amdgcn_readfirstlane((int)(size_t)smem + r * PITCH);
       asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
                    :
@@ -467,19 +492,39 @@ __device__ __forceinline__ void update_tile_staged(const f32x16 (&acc)[TM][TN], 
 #pragma unroll
           for (int rg = 0; rg < 4; ++rg) {
             const int nl = wn0 + j * 32 + 8 * rg + 4 * (l >> 5);
-            const int gnn = n0 + nl;
-            if (gm < M && gnn < N) {
-              const f32x4 w = *reinterpret_cast<const f32x4*>(smem + ml * PITCH + nl * 4);
-              const f32x4 a = {acc[i][j][4 * rg], acc[i][j][4 * rg + 1], acc[i][j][4 * rg + 2], acc[i][j][4 * rg + 3]};
-              f32x4 r;
+            f32x4* p = reinterpret_cast<f32x4*>(smem + ml * PITCH + nl * 4);
+            const f32x4 w = *p;
+            f32x4 a = {acc[i][j][4 * rg], acc[i][j][4 * rg + 1], acc[i][j][4 * rg + 2], acc[i][j][4 * rg + 3]};
+            f32x4 r;
+            if (MODE == 0) {
               r.x = __fmaf_rn(-e.eta, a.x, w.x); r.y = __fmaf_rn(-e.eta, a.y, w.y);
               r.z = __fmaf_rn(-e.eta, a.z, w.z); r.w = __fmaf_rn(-e.eta, a.w, w.w);
-              const int64_t o = (int64_t)gm * e.ldo + gnn;
-              *reinterpret_cast<f32x4*>(e.upd_w + o) = r;
-              u32x2 v; v.x = rv_pack_bf16x2(r.x, r.y); v.y = rv_pack_bf16x2(r.z, r.w);
-              *reinterpret_cast<u32x2*>((uint16_t*)e.out2 + o) = v;
-              if (e.out) *reinterpret_cast<f32x4*>((float*)e.out + o) = a;
+              if (e.out && gm < M && n0 + nl < N)
+                *reinterpret_cast<f32x4*>((float*)e.out + (int64_t)gm * e.ldo + n0 + nl) = a;
+            } else {
+              add_bias4(a, bias4[j][rg]);
+              r = a + w;
             }
+            *p = r;
+          }
+        }
+      }
+    }
+    __syncthreads();   // the half's results are in LDS
+#pragma unroll 1
+    for (int rb = 0; rb < RPW; rb += 8) {
+      f32x4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const f32x4*>(smem + (wave + (rb + u) * NW) * PITCH + l * 16);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int gm = m0 + h * HALF + wave + (rb + u) * NW;
+        if (gm < M && col_ok) {
+          const int64_t o = (int64_t)gm * e.ldo + gn;
+          *reinterpret_cast<f32x4*>(dst32 + o) = v[u];
+          if (BF16OUT) {
+            u32x2 q; q.x = rv_pack_bf16x2(v[u].x, v[u].y); q.y = rv_pack_bf16x2(v[u].z, v[u].w);
+            *reinterpret_cast<u32x2*>((uint16_t*)e.out2 + o) = q;
           }
         }
       }
@@ -705,8 +750,10 @@ __device__ __forceinline__ void gemm_dtl_body(const uint16_t* __restrict__ A, in
   if constexpr (staged_epi(EPI)) {
     write_tile_staged<BM, BN, 64 * NW, TM, TN, EPI>(acc, e, m0, n0, wm0, wn0, M, N, smem);
   } else if constexpr (EPI == EPI_F32_UPD) {
-    if (e.upd_w) update_tile_staged<BM, BN, NW, TM, TN>(acc, e, m0, n0, wm0, wn0, M, N, smem);   // workgroup-uniform
+    if (e.upd_w) f32_tile_through_lds<BM, BN, NW, TM, TN, 0, true>(acc, e, m0, n0, wm0, wn0, M, N, smem);   // workgroup-uniform
     else write_tile<TM, TN, EPI>(acc, e, m0 + wm0, n0 + wn0, M, N);
+  } else if constexpr (epi_has_resid(EPI) && PIPELINED && RV_RESID_LDS) {
+    f32_tile_through_lds<BM, BN, NW, TM, TN, 1, EPI == EPI_F32_BIAS_RESID_BF16>(acc, e, m0, n0, wm0, wn0, M, N, smem);
   } else {
     write_tile<TM, TN, EPI>(acc, e, m0 + wm0, n0 + wn0, M, N);
   }
@@ -762,7 +809,8 @@ template <int BM, int BN, int BK, int NS, int NW, int WPE, bool AKM, bool BKM, i
 rv_status launch_dtl(const rv_gemm_args& g, hipStream_t st) {
   constexpr int ring = NS * (dtl_tile_bytes(BM, BK) + dtl_tile_bytes(BN, BK));
   // the GELU' epilogue keeps two rows of fp32 column sums (one per wave row) behind the image
-  constexpr int image = staged_epi(EPI) ? BM * stage_pitch(BN) + (EPI == EPI_BF16_DGELU ? 2 * BN * 4 : 0) : 0;
+  constexpr int image = staged_epi(EPI) ? BM * stage_pitch(BN) + (EPI == EPI_BF16_DGELU ? 2 * BN * 4 : 0)
+                        : (epi_has_resid(EPI) && NW == 8 && BM == 256 && BN == 256 ? upd_image_bytes(BM, BN) : 0);
   constexpr int smem = ring > image ? ring : image;
   auto kern = gemm_dtl_kernel<BM, BN, BK, NS, NW, WPE, AKM, BKM, EPI>;
   // once per instantiation; a function-local static is initialised exactly once, also under threads
