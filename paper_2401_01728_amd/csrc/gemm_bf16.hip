@@ -182,7 +182,7 @@ __device__ __forceinline__ void write_tile(const f32x16 (&acc)[TM][TN], const Ep
 // XCD has its own L2.  First give every XCD a CONTIGUOUS range of tile numbers, then walk
 // that range in bands of 8 tile-rows, column by column: the ~32 tiles an XCD has in flight
 // form an 8 x 4 patch, so it pulls 12 operand tiles per k-step through its L2 instead of 33.
-__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& bm, int& bn) {
+__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int band_rows, int& bm, int& bn) {
   const int total = tiles_m * tiles_n;
   int id = blockIdx.x;
   if (tiles_m < 0) {   // natural order: consecutive workgroups walk down one column of tiles
@@ -190,7 +190,7 @@ __device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& bm,
   }
   const int per = total / 8;
   if (id < per * 8) id = (id % 8) * per + id / 8;       // the remainder keeps its natural order
-  constexpr int GM = 8;
+  const int GM = band_rows;
   const int band = id / (GM * tiles_n);
   const int first = band * GM;
   const int rows = tiles_m - first < GM ? tiles_m - first : GM;
@@ -762,9 +762,10 @@ __device__ __forceinline__ void gemm_dtl_body(const uint16_t* __restrict__ A, in
 template <int BM, int BN, int BK, int NS, int NW, int WPE, bool AKM, bool BKM, int EPI>
 __global__ __launch_bounds__(64 * NW, WPE) void gemm_dtl_kernel(const uint16_t* __restrict__ A, int64_t lda,
                                                                  const uint16_t* __restrict__ B, int64_t ldb,
-                                                                 int M, int N, int K, int tiles_m, int tiles_n, Epi e) {
+                                                                 int M, int N, int K, int tiles_m, int tiles_n,
+                                                                 int band_rows, Epi e) {
   int bm, bn;
-  tile_of_block(tiles_m, tiles_n, bm, bn);
+  tile_of_block(tiles_m, tiles_n, band_rows, bm, bn);
   gemm_dtl_body<BM, BN, BK, NS, NW, AKM, BKM, EPI>(A, lda, B, ldb, M, N, K, bm, bn, e);
 }
 
@@ -821,9 +822,17 @@ rv_status launch_dtl(const rv_gemm_args& g, hipStream_t st) {
   Epi e{g.out, g.ldo, g.out2, g.bias, g.resid, g.ldr, g.zin, nullptr, 0.f, g.epi == EPI_BF16_DGELU ? g.colpart : nullptr};
   g.colpart_rows = (g.M + BM - 1) / BM;
   const int ntiles = tm * tn;
-  if (!(BM == 128 && BN == 128)) tm = -tm;   // measured: the XCD-banded map pays only for the small tile
+  // Measured: alone, the XCD-banded map pays only for the small tile.  Inside a stage step a
+  // launch holds about a third of every XCD's CUs, and what an XCD runs of it at one time should
+  // share operand panels: bands of 8 tile rows (2 for 32 or more tile rows) against the natural
+  // order: stage steps -1.3 % / -0.6 % / -1.1 % (configs 5 / 3 / 2).
+  int band = 8;
+  if (!(BM == 128 && BN == 128)) {
+    if (g.sharing == 0) tm = -tm;
+    else band = tm >= 32 ? 2 : 8;
+  }
   hipLaunchKernelGGL(kern, dim3(ntiles), dim3(64 * NW), smem, st, g.A, g.lda, g.B, g.ldb, g.M, g.N, g.K,
-                     tm, tn, e);
+                     tm, tn, band, e);
   return rv_launch_status();
 }
 
