@@ -824,13 +824,11 @@ rv_status launch_dtl(const rv_gemm_args& g, hipStream_t st) {
   const int ntiles = tm * tn;
   // Measured: alone, the XCD-banded map pays only for the small tile.  Inside a stage step a
   // launch holds about a third of every XCD's CUs, and what an XCD runs of it at one time should
-  // share operand panels: bands of 8 tile rows (2 for 32 or more tile rows) against the natural
-  // order: stage steps -1.3 % / -0.6 % / -1.1 % (configs 5 / 3 / 2).
+  // share operand panels: bands of 8 tile rows (2 for 32 or more tile rows, either tile size)
+  // against the natural order: stage steps -1.3 % / -0.6 % / -1.9 % (configs 5 / 3 / 2).
   int band = 8;
-  if (!(BM == 128 && BN == 128)) {
-    if (g.sharing == 0) tm = -tm;
-    else band = tm >= 32 ? 2 : 8;
-  }
+  if (g.sharing != 0) band = tm >= 32 ? 2 : 8;
+  else if (!(BM == 128 && BN == 128)) tm = -tm;
   hipLaunchKernelGGL(kern, dim3(ntiles), dim3(64 * NW), smem, st, g.A, g.lda, g.B, g.ldb, g.M, g.N, g.K,
                      tm, tn, band, e);
   return rv_launch_status();
