@@ -108,9 +108,9 @@ constexpr int kBwdWaves = 4;
 // on the way instead of one row's.  What bounds the choice is 80 registers per lane: one such
 // wave per SIMD (and a few hundred bytes of LDS) still fits beside the two ~210-register waves
 // of a matrix-product kernel of another stream, so the HBM-bound backward runs under the
-// MFMA-bound products instead of waiting for a free CU.  NV = 1, RF = 2 for d <= 1024 (RF = 4
-// spills and measured 2 % slower in the stage step); NV = 2, RF = 1 up to 2048; NV = 4 beyond
-// (no such stage is benchmarked).  Row statistics are combined
+// MFMA-bound products instead of waiting for a free CU.  This kernel serves d > 1024: NV = 2,
+// RF = 1 up to 2048; NV = 4 beyond (no such stage is benchmarked); d <= 1024 takes
+// ln_bwd_pipe_kernel below, which keeps twice the rows in flight.  Row statistics are combined
 // through LDS in a fixed order, one barrier per RF rows, two alternating slots.  The column sums
 // stay in registers for the workgroup's 16 rows and leave as one partial row per workgroup.
 template <int NV, int RF>
@@ -202,6 +202,147 @@ __global__ __launch_bounds__(64 * kBwdWaves, NV <= 2 ? 6 : 1) void ln_bwd_kernel
       }
     }
   }
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int c = cbase + 256 * i;
+    if (c < d) {
+      *reinterpret_cast<f32x4*>(part + ((int64_t)blockIdx.x * 3 + 0) * d + c) = ag[i];
+      *reinterpret_cast<f32x4*>(part + ((int64_t)blockIdx.x * 3 + 1) * d + c) = ab[i];
+      *reinterpret_cast<f32x4*>(part + ((int64_t)blockIdx.x * 3 + 2) * d + c) = ax[i];
+    }
+  }
+}
+
+// The butterfly of wave_sum without lane-address registers: the two 32-lane halves are exchanged
+// with v_permlane32_swap, the rest with ds_swizzle's immediate patterns.  Same pairs, same sums.
+__device__ __forceinline__ float wave_sum_imm(float v) {
+  const auto h = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = __uint_as_float(h[0]) + __uint_as_float(h[1]);
+  v += __uint_as_float(__builtin_amdgcn_ds_swizzle(__float_as_uint(v), (16 << 10) | 0x1F));
+  v += __uint_as_float(__builtin_amdgcn_ds_swizzle(__float_as_uint(v), (8 << 10) | 0x1F));
+  v += __uint_as_float(__builtin_amdgcn_ds_swizzle(__float_as_uint(v), (4 << 10) | 0x1F));
+  v += __uint_as_float(__builtin_amdgcn_ds_swizzle(__float_as_uint(v), (2 << 10) | 0x1F));
+  v += __uint_as_float(__builtin_amdgcn_ds_swizzle(__float_as_uint(v), (1 << 10) | 0x1F));
+  return v;
+}
+// The same arithmetic, in the same order, with the next RF rows' operands already requested
+// while the current RF rows are reduced, combined and stored: two sets of row registers
+// alternate, so 2 * RF rows are on the way per workgroup.  Beside a matrix-product kernel only
+// one such workgroup fits on a CU, and what it has in flight is what bounds it.  For d <= 1024
+// (NV = 1, RF = 2) both sets fit in 81 registers and the stage step of the 1024-wide stage
+// measured 0.5 % shorter.  For 1024 < d <= 2048 two sets and the 24 column-sum registers do not
+// fit in the 96 registers that are free beside two ~200-register waves; with the column sums
+// moved to LDS they did, and the 1600-wide stage steps measured within +-0.2 % of
+// ln_bwd_kernel<2, 1>, which therefore stays.
+template <int NV, int RF>
+struct LnRows {
+  f32x4 xh[RF][NV], rs[RF][NV];
+  u32x2 dy[RF][NV];
+  float mu[RF], r[RF];
+};
+template <int NV, int RF>
+__global__ __launch_bounds__(64 * kBwdWaves, 5) void ln_bwd_pipe_kernel(const uint16_t* __restrict__ dy,
+                                                                const float* __restrict__ x,
+                                                                const float* __restrict__ mean,
+                                                                const float* __restrict__ rstd,
+                                                                const uint16_t* __restrict__ gamma,
+                                                                const float* dres, float* dx,
+                                                                uint16_t* __restrict__ dx_bf16,
+                                                                float* __restrict__ part, int T, int d) {
+  constexpr int CS = kBwdWaves;
+  constexpr int G = kRowsPerBlock / RF;
+  static_assert(G % 2 == 0, "row groups alternate between two register sets");
+  __shared__ float stat[2][RF][CS][2];
+  const int cs = threadIdx.x >> 6, l = threadIdx.x & 63;
+  const int cbase = cs * (NV * 256) + l * 4;
+  f32x4 ag[NV], ab[NV], ax[NV], gam[NV];
+  unsigned cb[NV];   // byte offset of the lane's fp32 column group in a row
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    ag[i] = 0.f; ab[i] = 0.f; ax[i] = 0.f;
+    const int c = cbase + 256 * i;
+    cb[i] = (unsigned)(c < d ? c : d - 4) * 4u;
+    gam[i] = bf16x4_to_f32(*reinterpret_cast<const u32x2*>(gamma + (cb[i] >> 2)));
+    if (c >= d) gam[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  // every lane loads: rows past the end re-read the last row, columns past the end the row's last
+  // four; neither is used
+  auto request = [&](LnRows<NV, RF>& w, int row0) {
+#pragma unroll
+    for (int q = 0; q < RF; ++q) {
+      const int row = row0 + q < T ? row0 + q : T - 1;
+      w.mu[q] = mean[row]; w.r[q] = rstd[row];
+      // uniform row bases plus a 32-bit lane offset: no 64-bit address registers per load
+      const char* xr = reinterpret_cast<const char*>(x + (int64_t)row * d);
+      const char* rr = reinterpret_cast<const char*>(dres + (int64_t)row * d);
+      const char* yr = reinterpret_cast<const char*>(dy + (int64_t)row * d);
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        w.xh[q][i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(xr + cb[i]));
+        w.rs[q][i] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(rr + cb[i]));
+        w.dy[q][i] = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(yr + (cb[i] >> 1)));
+      }
+    }
+  };
+  auto finish = [&](LnRows<NV, RF>& w, int row0, int k) {
+#pragma unroll
+    for (int q = 0; q < RF; ++q) {
+      float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+      for (int i = 0; i < NV; ++i) {
+        w.xh[q][i] = (w.xh[q][i] - w.mu[q]) * w.r[q];
+        const f32x4 dxh = bf16x4_to_f32(w.dy[q][i]) * gam[i];   // zero in columns past the end
+        const f32x4 t = dxh * w.xh[q][i];
+        s1 += (dxh.x + dxh.y) + (dxh.z + dxh.w);
+        s2 += (t.x + t.y) + (t.z + t.w);
+      }
+      s1 = wave_sum_imm(s1); s2 = wave_sum_imm(s2);
+      if (l == 0) { stat[k & 1][q][cs][0] = s1; stat[k & 1][q][cs][1] = s2; }
+      // dy is widened again after the barrier rather than kept as fp32 across it (registers)
+#pragma unroll
+      for (int i = 0; i < NV; ++i) asm volatile("" : "+v"(w.dy[q][i].x), "+v"(w.dy[q][i].y));
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < RF; ++q) {
+      const int row = row0 + q;
+      float s1 = stat[k & 1][q][0][0], s2 = stat[k & 1][q][0][1];
+#pragma unroll
+      for (int w2 = 1; w2 < CS; ++w2) { s1 += stat[k & 1][q][w2][0]; s2 += stat[k & 1][q][w2][1]; }
+      const float c1 = s1 / (float)d, c2 = s2 / (float)d;
+      if (row < T) {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+          const int c = cbase + 256 * i;
+          if (c < d) {
+            const f32x4 dyv = bf16x4_to_f32(w.dy[q][i]);
+            const f32x4 dxh = dyv * gam[i];
+            const f32x4 o = (dxh - c1 - w.xh[q][i] * c2) * w.r[q] + w.rs[q][i];
+            __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(reinterpret_cast<char*>(dx + (int64_t)row * d) + cb[i]));
+            if (dx_bf16)
+              __builtin_nontemporal_store(f32_to_bf16x4(o), reinterpret_cast<u32x2*>(reinterpret_cast<char*>(dx_bf16 + (int64_t)row * d) + (cb[i] >> 1)));
+            ag[i] += dyv * w.xh[q][i];
+            ab[i] += dyv;
+            ax[i] += o;
+          }
+          if (NV > 1) __builtin_amdgcn_sched_barrier(0);   // one column group's temporaries at a time
+        }
+      }
+    }
+  };
+  const int rowb = blockIdx.x * kRowsPerBlock;
+  LnRows<NV, RF> wa, wb;
+  request(wa, rowb);
+#pragma unroll 1
+  for (int k = 0; k < G - 2; k += 2) {
+    request(wb, rowb + (k + 1) * RF);
+    finish(wa, rowb + k * RF, k);
+    request(wa, rowb + (k + 2) * RF);
+    finish(wb, rowb + (k + 1) * RF, k + 1);
+  }
+  request(wb, rowb + (G - 1) * RF);
+  finish(wa, rowb + (G - 2) * RF, G - 2);
+  finish(wb, rowb + (G - 1) * RF, G - 1);
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
     const int c = cbase + 256 * i;
@@ -322,7 +463,9 @@ rv_status rv_ln_bwd(const uint16_t* dy, const float* x, const float* mean, const
   dim3 grid(rv_ln_bwd_parts(T)), blk(64 * kBwdWaves);
 #define RV_LN_BWD(NV, RF) \
   hipLaunchKernelGGL((ln_bwd_kernel<NV, RF>), grid, blk, 0, st, dy, x, mean, rstd, gamma, dres, dx, dx_bf16, part, T, d);
-  if (d <= 1024) { RV_LN_BWD(1, 2) }
+  if (d <= 1024) {
+    hipLaunchKernelGGL((ln_bwd_pipe_kernel<1, 2>), grid, blk, 0, st, dy, x, mean, rstd, gamma, dres, dx, dx_bf16, part, T, d);
+  }
   else if (d <= 2048) { RV_LN_BWD(2, 1) }
   else { RV_LN_BWD(4, 1) }
 #undef RV_LN_BWD
