@@ -67,7 +67,7 @@ rv_status rv_k_layernorm_fwd(const void* x, int x_is_bf16, float* xcopy, const v
  *   dx = dres + rstd * (dxh - mean(dxh) - xh * mean(dxh * xh)),  dxh = dy * gamma
  * dy bf16 [T,d]; x, dres, dx fp32 [T,d] (dx may alias dres); dx_bf16 optional bf16 copy.
  * Column sums over tokens: dgamma = sum dy*xh, dbeta = sum dy, dbias = sum dx (each fp32
- * [d], each optional).  part: scratch of ceil(T/16)*3*d floats.  d <= 4096.
+ * [d], each optional).  part: scratch of ceil(T/8)*3*d floats.  d <= 4096.
  */
 rv_status rv_k_layernorm_bwd(const void* dy, const float* x, const float* mean, const float* rstd,
                              const void* gamma, const float* dres, float* dx, void* dx_bf16,

@@ -76,7 +76,7 @@ rv_status rv_dec_plan(rv_stage* s) {
   for (size_t& o : p->w_dz) { o = w; w += align_up(T * f * 2); }
   for (size_t& o : p->w_dqkv) { o = w; w += align_up(T * 3 * d * 2); }
   p->w_D = w; w += align_up(T * H * 4);
-  const size_t part_ln = (size_t)rv_ln_bwd_parts(p->T) * 3 * d;
+  const size_t part_ln = (size_t)rv_ln_bwd_parts(p->T, d) * 3 * d;
   for (auto& pair : p->w_part_ln)
     for (size_t& o : pair) { o = w; w += align_up(part_ln * 4); }
   // partial rows of the bias gradients: of the arriving gradient (32-row blocks), of dz (one per tile
@@ -163,7 +163,7 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
   float* dres = (float*)(s->work + p.w_dres);
   uint16_t* dtmp = (uint16_t*)(s->work + p.w_dtmp);
   float* Dbuf = (float*)(s->work + p.w_D);
-  const int ln_parts = rv_ln_bwd_parts(T);
+  const int ln_parts = rv_ln_bwd_parts(T, d);
   // fused update (plain Eq. 2): every kernel that completes a parameter gradient applies it at once
   // to the fp32 master and writes the bf16 rounding into the new weight version `vdst`
   uint16_t* vdst = s->fused ? (uint16_t*)s->ver[s->upd_dst] : nullptr;

@@ -53,7 +53,7 @@ rv_status rv_gemm_wgrad_grouped(const rv_gemm_args* gs, int count, hipStream_t s
 // ---- norm.hip ---------------------------------------------------------------------
 rv_status rv_ln_fwd(const void* x, int x_is_bf16, float* xcopy, const uint16_t* gamma, const uint16_t* beta,
                     uint16_t* y, float* mean, float* rstd, int T, int d, float eps, hipStream_t st);
-int rv_ln_bwd_parts(int T);   // partial rows written by rv_ln_bwd (each 3*d floats)
+int rv_ln_bwd_parts(int T, int d);   // partial rows written by rv_ln_bwd (each 3*d floats)
 rv_status rv_ln_bwd(const uint16_t* dy, const float* x, const float* mean, const float* rstd,
                     const uint16_t* gamma, const float* dres, float* dx, uint16_t* dx_bf16, float* part,
                     int T, int d, hipStream_t st);

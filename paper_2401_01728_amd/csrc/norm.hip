@@ -240,7 +240,7 @@ struct LnRows {
   u32x2 dy[RF][NV];
   float mu[RF], r[RF];
 };
-template <int NV, int RF>
+template <int NV, int RF, int ROWS>
 __global__ __launch_bounds__(64 * kBwdWaves, 5) void ln_bwd_pipe_kernel(const uint16_t* __restrict__ dy,
                                                                 const float* __restrict__ x,
                                                                 const float* __restrict__ mean,
@@ -250,8 +250,8 @@ __global__ __launch_bounds__(64 * kBwdWaves, 5) void ln_bwd_pipe_kernel(const ui
                                                                 uint16_t* __restrict__ dx_bf16,
                                                                 float* __restrict__ part, int T, int d) {
   constexpr int CS = kBwdWaves;
-  constexpr int G = kRowsPerBlock / RF;
-  static_assert(G % 2 == 0, "row groups alternate between two register sets");
+  constexpr int G = ROWS / RF;
+  static_assert(ROWS % RF == 0 && G % 2 == 0, "row groups alternate between two register sets");
   __shared__ float stat[2][RF][CS][2];
   const int cs = threadIdx.x >> 6, l = threadIdx.x & 63;
   const int cbase = cs * (NV * 256) + l * 4;
@@ -330,7 +330,7 @@ __global__ __launch_bounds__(64 * kBwdWaves, 5) void ln_bwd_pipe_kernel(const ui
       }
     }
   };
-  const int rowb = blockIdx.x * kRowsPerBlock;
+  const int rowb = blockIdx.x * ROWS;
   LnRows<NV, RF> wa, wb;
   request(wa, rowb);
 #pragma unroll 1
@@ -453,18 +453,25 @@ rv_status rv_ln_fwd(const void* x, int x_is_bf16, float* xcopy, const uint16_t* 
   return rv_launch_status();
 }
 
-int rv_ln_bwd_parts(int T) { return (T + kRowsPerBlock - 1) / kRowsPerBlock; }
+// Rows per workgroup: 8 for d <= 1024 (twice the workgroups: the stage step of the 1024-wide stage
+// measured 0.4 % shorter than with 16, and 0.9 % shorter than with 4), 16 beyond (8 measured
+// -0.2 % at d = 1600 and +0.2 % at d = 2048).
+constexpr int kPipeRows = 8;
+int rv_ln_bwd_parts(int T, int d) {
+  const int rows = d <= 1024 ? kPipeRows : kRowsPerBlock;
+  return (T + rows - 1) / rows;
+}
 
 rv_status rv_ln_bwd(const uint16_t* dy, const float* x, const float* mean, const float* rstd,
                     const uint16_t* gamma, const float* dres, float* dx, uint16_t* dx_bf16, float* part,
                     int T, int d, hipStream_t st) {
   if (!dy || !x || !mean || !rstd || !gamma || !dres || !dx || !part || T < 1 || d < 4 || d % 4 || d > 4096)
     return RV_E_INVAL;
-  dim3 grid(rv_ln_bwd_parts(T)), blk(64 * kBwdWaves);
+  dim3 grid(rv_ln_bwd_parts(T, d)), blk(64 * kBwdWaves);
 #define RV_LN_BWD(NV, RF) \
   hipLaunchKernelGGL((ln_bwd_kernel<NV, RF>), grid, blk, 0, st, dy, x, mean, rstd, gamma, dres, dx, dx_bf16, part, T, d);
   if (d <= 1024) {
-    hipLaunchKernelGGL((ln_bwd_pipe_kernel<1, 2>), grid, blk, 0, st, dy, x, mean, rstd, gamma, dres, dx, dx_bf16, part, T, d);
+    hipLaunchKernelGGL((ln_bwd_pipe_kernel<1, 2, kPipeRows>), grid, blk, 0, st, dy, x, mean, rstd, gamma, dres, dx, dx_bf16, part, T, d);
   }
   else if (d <= 2048) { RV_LN_BWD(2, 1) }
   else { RV_LN_BWD(4, 1) }
@@ -516,7 +523,7 @@ extern "C" rv_status rv_k_layernorm_bwd(const void* dy, const float* x, const fl
   hipStream_t st = (hipStream_t)stream;
   RV_TRY(rv_ln_bwd((const uint16_t*)dy, x, mean, rstd, (const uint16_t*)gamma, dres, dx, (uint16_t*)dx_bf16,
                    part, T, d, st));
-  const int R = rv_ln_bwd_parts(T);
+  const int R = rv_ln_bwd_parts(T, d);
   const float* src[3]; float* out[3]; int n = 0;
   if (dgamma) { src[n] = part; out[n++] = dgamma; }
   if (dbeta) { src[n] = part + d; out[n++] = dbeta; }

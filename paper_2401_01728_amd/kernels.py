@@ -45,7 +45,7 @@ def layernorm_bwd(dy, x, mean, rstd, gamma, dres, want_bf16=True, stream=None):
     T, d = x.shape
     dx = torch.empty(T, d, dtype=torch.float32, device="cuda")
     dx16 = torch.empty(T, d, dtype=torch.bfloat16, device="cuda") if want_bf16 else None
-    part = torch.empty(((T + 15) // 16) * 3 * d, dtype=torch.float32, device="cuda")
+    part = torch.empty(((T + 7) // 8) * 3 * d, dtype=torch.float32, device="cuda")
     dg, db, dbias = (torch.empty(d, dtype=torch.float32, device="cuda") for _ in range(3))
     _check(_lib.lib().rv_k_layernorm_bwd(_ptr(dy), _ptr(x), _ptr(mean), _ptr(rstd), _ptr(gamma), _ptr(dres),
                                          _ptr(dx), _ptr(dx16), _ptr(part), _ptr(dg), _ptr(db), _ptr(dbias), T, d,
