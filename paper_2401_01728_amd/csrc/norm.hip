@@ -26,6 +26,19 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
+// The butterfly of wave_sum without lane-address registers: the two 32-lane halves are exchanged
+// with v_permlane32_swap, the rest with ds_swizzle's immediate patterns.  Same pairs, same sums.
+__device__ __forceinline__ float wave_sum_imm(float v) {
+  const auto h = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = __uint_as_float(h[0]) + __uint_as_float(h[1]);
+  v += __uint_as_float(__builtin_amdgcn_ds_swizzle(__float_as_uint(v), (16 << 10) | 0x1F));
+  v += __uint_as_float(__builtin_amdgcn_ds_swizzle(__float_as_uint(v), (8 << 10) | 0x1F));
+  v += __uint_as_float(__builtin_amdgcn_ds_swizzle(__float_as_uint(v), (4 << 10) | 0x1F));
+  v += __uint_as_float(__builtin_amdgcn_ds_swizzle(__float_as_uint(v), (2 << 10) | 0x1F));
+  v += __uint_as_float(__builtin_amdgcn_ds_swizzle(__float_as_uint(v), (1 << 10) | 0x1F));
+  return v;
+}
+
 __device__ __forceinline__ f32x4 bf16x4_to_f32(u32x2 b) {
   f32x4 r;
   r.x = __uint_as_float(b.x << 16); r.y = __uint_as_float(b.x & 0xFFFF0000u);
@@ -91,6 +104,84 @@ __global__ __launch_bounds__(kThreads, NV <= 8 ? 6 : 1) void ln_fwd_kernel(const
     const f32x4 o = (v[i] - mu) * r * g + b;
     if (c < d) *reinterpret_cast<u32x2*>(y + (int64_t)row * d + c) = f32_to_bf16x4(o);
   }
+}
+
+// The fp32-input forward with RPW rows per wave and two alternating sets of row registers: the
+// next row is requested before the current one is reduced and stored, so a wave keeps two rows
+// on the way instead of one.  Used up to d = 1792 (seven column groups: two sets fit the 96
+// registers that are free beside a matrix-product kernel, but for nine spilled dwords; with eight
+// groups the spills cost the 2048-wide stage step 1.6 %).  RPW is chosen so that a launch has about
+// two workgroups per CU: 4 from 8192 rows on, else 2 - stage steps -0.5 % (d = 1600, 8192 rows)
+// and -0.25 % (d = 1024, 4096 rows); the other choice measured +0.2 % / +0.3 %.
+template <int NV, int RPW>
+__global__ __launch_bounds__(kThreads, 5) void ln_fwd_pipe_kernel(const float* __restrict__ xin,
+                                                                  const uint16_t* __restrict__ gamma,
+                                                                  const uint16_t* __restrict__ beta,
+                                                                  uint16_t* __restrict__ y,
+                                                                  float* __restrict__ mean,
+                                                                  float* __restrict__ rstd, int T, int d,
+                                                                  float eps) {
+  static_assert(RPW % 2 == 0, "rows alternate between two register sets");
+  const int wave = threadIdx.x >> 6, l = threadIdx.x & 63;
+  const int row0 = (blockIdx.x * kWaves + wave) * RPW;
+  if (row0 >= T) return;
+  // byte offset of the lane's i-th fp32 column group in a row (clamped past the end); recomputed
+  // where it is used: NV registers less
+  auto cbo = [&](int i) -> unsigned {
+    const int c = l * 4 + 256 * i;
+    return (unsigned)(c < d ? c : d - 4) * 4u;
+  };
+  auto request = [&](f32x4 (&v)[NV], int row) {
+    const char* xr = reinterpret_cast<const char*>(xin + (int64_t)(row < T ? row : T - 1) * d);
+#pragma unroll
+    for (int i = 0; i < NV; ++i) v[i] = *reinterpret_cast<const f32x4*>(xr + cbo(i));
+  };
+  auto finish = [&](f32x4 (&v)[NV], int row) {
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      if (l * 4 + 256 * i >= d) v[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+      s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+    }
+    const float mu = wave_sum_imm(s) / (float)d;
+    float q = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      if (l * 4 + 256 * i < d) {
+        f32x4 t = v[i] - mu;
+        q += (t.x * t.x + t.y * t.y) + (t.z * t.z + t.w * t.w);
+      }
+    }
+    const float r = rsqrtf(wave_sum_imm(q) / (float)d + eps);
+    if (row >= T) return;
+    if (l == 0) { mean[row] = mu; rstd[row] = r; }
+    char* yr = reinterpret_cast<char*>(y + (int64_t)row * d);
+    // gamma and beta are fetched again for every row (they stay in cache) rather than held in
+    // 4 * NV registers across rows
+    const char* gp = reinterpret_cast<const char*>(gamma);
+    const char* bp = reinterpret_cast<const char*>(beta);
+    asm volatile("" : "+s"(gp), "+s"(bp));
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const f32x4 g = bf16x4_to_f32(*reinterpret_cast<const u32x2*>(gp + (cbo(i) >> 1)));
+      const f32x4 b = bf16x4_to_f32(*reinterpret_cast<const u32x2*>(bp + (cbo(i) >> 1)));
+      const f32x4 o = (v[i] - mu) * r * g + b;
+      if (l * 4 + 256 * i < d) *reinterpret_cast<u32x2*>(yr + (cbo(i) >> 1)) = f32_to_bf16x4(o);
+      if (NV > 4 && i % 4 == 3) __builtin_amdgcn_sched_barrier(0);   // gamma/beta of four column groups at a time
+    }
+  };
+  f32x4 va[NV], vb[NV];
+  request(va, row0);
+#pragma unroll 1
+  for (int k = 0; k < RPW - 2; k += 2) {
+    request(vb, row0 + k + 1);
+    finish(va, row0 + k);
+    request(va, row0 + k + 2);
+    finish(vb, row0 + k + 1);
+  }
+  request(vb, row0 + RPW - 1);
+  finish(va, row0 + RPW - 2);
+  finish(vb, row0 + RPW - 1);
 }
 
 // Backward of y = LN(x)*gamma + beta joined with the residual branch:
@@ -213,18 +304,6 @@ __global__ __launch_bounds__(64 * kBwdWaves, NV <= 2 ? 6 : 1) void ln_bwd_kernel
   }
 }
 
-// The butterfly of wave_sum without lane-address registers: the two 32-lane halves are exchanged
-// with v_permlane32_swap, the rest with ds_swizzle's immediate patterns.  Same pairs, same sums.
-__device__ __forceinline__ float wave_sum_imm(float v) {
-  const auto h = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-  v = __uint_as_float(h[0]) + __uint_as_float(h[1]);
-  v += __uint_as_float(__builtin_amdgcn_ds_swizzle(__float_as_uint(v), (16 << 10) | 0x1F));
-  v += __uint_as_float(__builtin_amdgcn_ds_swizzle(__float_as_uint(v), (8 << 10) | 0x1F));
-  v += __uint_as_float(__builtin_amdgcn_ds_swizzle(__float_as_uint(v), (4 << 10) | 0x1F));
-  v += __uint_as_float(__builtin_amdgcn_ds_swizzle(__float_as_uint(v), (2 << 10) | 0x1F));
-  v += __uint_as_float(__builtin_amdgcn_ds_swizzle(__float_as_uint(v), (1 << 10) | 0x1F));
-  return v;
-}
 // The same arithmetic, in the same order, with the next RF rows' operands already requested
 // while the current RF rows are reduced, combined and stored: two sets of row registers
 // alternate, so 2 * RF rows are on the way per workgroup.  Beside a matrix-product kernel only
@@ -438,6 +517,16 @@ rv_status rv_ln_fwd(const void* x, int x_is_bf16, float* xcopy, const uint16_t* 
   const int nv = nv_for(d);
   if (!nv) return RV_E_INVAL;
   dim3 grid((T + kWaves - 1) / kWaves), blk(kThreads);
+  if (!x_is_bf16 && d <= 1792) {
+    const int rpw = T >= 8192 ? 4 : 2;
+    dim3 g2((T + kWaves * rpw - 1) / (kWaves * rpw));
+#define RV_LN_FWDP(NV, RPW) \
+  hipLaunchKernelGGL((ln_fwd_pipe_kernel<NV, RPW>), g2, blk, 0, st, (const float*)x, gamma, beta, y, mean, rstd, T, d, eps);
+    if (nv == 4) { if (rpw == 4) { RV_LN_FWDP(4, 4) } else { RV_LN_FWDP(4, 2) } }
+    else { if (rpw == 4) { RV_LN_FWDP(7, 4) } else { RV_LN_FWDP(7, 2) } }
+#undef RV_LN_FWDP
+    return rv_launch_status();
+  }
 #define RV_LN_FWD(NV)                                                                                     \
   if (x_is_bf16)                                                                                          \
     hipLaunchKernelGGL((ln_fwd_kernel<NV, true>), grid, blk, 0, st, x, xcopy, gamma, beta, y, mean, rstd, T, d, eps); \
