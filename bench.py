@@ -184,8 +184,9 @@ def bench_stage(args, name, cpu_seconds=20.0):
         if len(blocks) >= 6 and time.perf_counter() - t_w0 > 3.0 and max(blocks[-4:]) <= 1.01 * min(blocks[-4:]):
             break
     # The dominant kernel of the step (largest share of its rocprofv3 trace) is the grouped
-    # weight-gradient launch of one block, dW2 | dW1 | dWo | dWqkv over the microbatch's tokens.
-    # The library brackets each of its launches with HIP events on the stream it goes to, here,
+    # weight-gradient kernel: dW2 | dW1 | dWo | dWqkv of one block over the microbatch's tokens, in
+    # one to three launches per block (the library decides when each product goes out).  The
+    # library brackets each of its launches with HIP events on the stream it goes to, here,
     # inside the timed steps, beside everything else the step has running.
     st.profile(True)
     ms, wall_ms, per = events_ms(step, args.steps, 0, args.reps)
@@ -194,7 +195,10 @@ def bench_stage(args, name, cpu_seconds=20.0):
     tokens = c["mb"] * c["S"]
     T, d, f = tokens, c["d"], c["f"]
     flops = decoder_flops_per_token(c) * tokens
-    kfl = 2.0 * T * (2 * d * f + 4 * d * d)
+    kfl_block = 2.0 * T * (2 * d * f + 4 * d * d)
+    blocks_timed = c["L"] * args.steps * args.reps
+    per_block = launches / float(blocks_timed) if launches else 1.0   # launches of that kernel per block
+    kfl = kfl_block / per_block                                        # mean flops of one launch
     kname = "gemm_dtl_grouped_wgrad_kernel"
     kshape = "%s: K=%d tokens, d=%d, ffn=%d" % (name, T, d, f)
     res = {"metric": "stage tokens/s (fwd+bwd+delayed SGD)", "value": tokens / (ms * 1e-3), "unit": "tokens/s",
@@ -204,9 +208,10 @@ def bench_stage(args, name, cpu_seconds=20.0):
            "wall_ms_per_step": wall_ms, "ms_per_step_reps": per,
            "warmup_steps_run": warm_steps, "cold_ms_per_step": blocks[0] if blocks else None}
     res["roofline"] = mfma_roofline(
-        kfl, k_us, kernel="%s (dW2, dW1, dWo, dWqkv of one block, K=%d tokens), inside the timed steps" % (kname, T),
+        kfl, k_us, kernel="%s (dW2, dW1, dWo, dWqkv of one block in %.3g launches, K=%d tokens), inside the timed steps" % (
+            kname, per_block, T),
         traffic=traffic_table().get((kname, kshape)), us_per_launch=k_us, launches_timed=launches,
-        algorithmic_flops_per_launch=kfl)
+        launches_per_block=per_block, algorithmic_flops_per_launch=kfl)
     # the whole step against the same peak: model flops of forward + backward (all kernels, three
     # streams) over the step time - the figure the 50 % target is about
     res["roofline_step"] = mfma_roofline(flops, ms * 1e3, algorithmic_flops_per_step=flops)
@@ -222,8 +227,8 @@ def bench_stage(args, name, cpu_seconds=20.0):
     dys = [grd(d), grd(f), grd(d), grd(3 * d)]
     outs = [torch.empty(x.shape[1], y.shape[1], dtype=torch.float32, device="cuda") for x, y in zip(xa, dys)]
     kms, _, _ = events_ms(lambda: kk.gemm_wgrad_grouped(xa, dys, outs), 20, 3, 3)
-    res["roofline_kernel_alone"] = mfma_roofline(kfl, kms * 1e3, kernel=kname + ", launched alone", us_per_launch=kms * 1e3,
-                                                 algorithmic_flops_per_launch=kfl)
+    res["roofline_kernel_alone"] = mfma_roofline(kfl_block, kms * 1e3, kernel=kname + ", the four products in one launch, alone",
+                                                 us_per_launch=kms * 1e3, algorithmic_flops_per_launch=kfl_block)
     # the largest forward product of a block (x W1 with the GELU epilogue), alone
     A = torch.empty(T, d, dtype=torch.bfloat16, device="cuda").normal_()
     B = torch.empty(d, f, dtype=torch.bfloat16, device="cuda").normal_(std=0.02)

@@ -258,9 +258,9 @@ rv_status rv_cluster_average_v(float* const* replicas, int C, size_t n, const in
 
 /*
  * Measurement aid (no part of the method): while on, a decoder stage brackets every launch of
- * the kernel that dominates its step - the grouped weight-gradient product dW2 | dW1 | dWo |
- * dWqkv of one block - with HIP events on the stream that launch goes to, inside whatever else
- * the step has running.  rv_stage_profile_read waits for the stage's streams, returns the number
+ * the kernel that dominates its step - the grouped weight-gradient product, which computes
+ * dW2 | dW1 | dWo | dWqkv of one block in one to three launches - with HIP events on the stream
+ * that launch goes to, inside whatever else the step has running.  rv_stage_profile_read waits for the stage's streams, returns the number
  * of launches bracketed since the last read and their mean duration in microseconds, and
  * forgets them.  Events are created per launch: keep it off outside measurements.
  */

@@ -202,6 +202,26 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
     RV_TRY(side_begin());
     RV_TRY(rv_reduce_rows(part_dy, rv_widen_parts(T), d, d, out, ws, upd(&out, 1)));
   }
+  // When the four weight-gradient products of a block go to the side stream.  Launch points:
+  // 0 behind the GELU' product (dz exists: dW2 and dW1 can run), 1 behind the second LayerNorm's
+  // backward (dx1 exists: dWo), 2 behind the attention backward (dqkv exists: all four).  One
+  // launch of all four at point 2 is the least launch work; going out earlier puts the products
+  // beside the chain's LayerNorm and attention kernels instead of beside its next products.
+  // Measured step time against the single launch, tiles of 256 x 256 on 256 CUs:
+  //   dW2 + dW1 at point 0, dWo + dWqkv at point 2:  -4.7 % where they are 512 and 256 tiles
+  //   (d 2048, ffn 8192), 0 % at 350 and 182 tiles (d 1600, ffn 6400), +1.3 % at 128 and 64 tiles
+  //   (d 1024, ffn 4096);
+  //   dWo on its own at point 1 as well:  -2.8 %, -1.2 %, +7 % in the same order.
+  // So: the feed-forward pair goes out early when it fills the chip at least once, and dWo leaves
+  // dWqkv only when the two together are not a whole number of rounds anyway.
+  const int kCUs = 256;
+  auto tiles = [](int M, int N) { return ((M + 255) / 256) * ((N + 255) / 256); };
+  const int n_ffn = 2 * tiles(d, f), n_o = tiles(d, d), n_qkv = tiles(d, 3 * d);
+  int wg_pos[4] = {2, 2, 2, 2};   // dW2, dW1, dWo, dWqkv
+  if (n_ffn >= kCUs) {
+    wg_pos[0] = wg_pos[1] = 0;
+    if ((n_o + n_qkv) % kCUs != 0) wg_pos[2] = 1;
+  }
   for (int l = p.L - 1; l >= 0; --l) {
     const int par = l & 1;
     // block l may overwrite what the side work of block l+2 read only after that is done
@@ -224,6 +244,26 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
     const uint16_t* z = (const uint16_t*)(sb + p.s_z);
     const uint16_t* g = (const uint16_t*)(sb + p.s_g);
     rv_gemm_args wg[4];
+    // the weight-gradient products whose launch point is `pos` go out as one grouped launch
+    auto side_launch = [&](int pos) -> rv_status {
+      rv_gemm_args grp[4];
+      int n = 0;
+      for (int k = 0; k < 4; ++k)
+        if (wg_pos[k] == pos) grp[n++] = wg[k];
+      if (!n) return RV_OK;
+      if (s->prof_on) {   // measurement aid: bracket the launch with events on its own stream
+        hipEvent_t e0 = nullptr, e1 = nullptr;
+        RV_HIP_TRY(hipEventCreate(&e0));
+        s->prof_ev.push_back(e0);
+        RV_HIP_TRY(hipEventCreate(&e1));
+        s->prof_ev.push_back(e1);
+        RV_HIP_TRY(hipEventRecord(e0, ws));
+        RV_TRY(rv_gemm_wgrad_grouped(grp, n, ws));
+        RV_HIP_TRY(hipEventRecord(e1, ws));
+        return RV_OK;
+      }
+      return rv_gemm_wgrad_grouped(grp, n, ws);
+    };
     auto wgrad = [&](int k, const uint16_t* A, int64_t lda, const uint16_t* B, int64_t ldb, int M, int N, float* out) {
       wg[k].A = A; wg[k].lda = lda; wg[k].a_kmajor = 1; wg[k].B = B; wg[k].ldb = ldb; wg[k].b_kmajor = 1;
       wg[k].M = M; wg[k].N = N; wg[k].K = T; wg[k].epi = RV_EPI_F32; wg[k].out = out; wg[k].ldo = N;
@@ -242,6 +282,7 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
                 part_dz, &dz_parts));
     wgrad(1, v2, d, dz, f, d, f, gl + p.w1);                                                         // dW1 = v2^T dz
     RV_TRY(side_begin());
+    RV_TRY(side_launch(0));
     {
       float* out = gl + p.b1;
       RV_TRY(rv_reduce_rows(part_dz, dz_parts, f, f, out, ws, upd(&out, 1)));
@@ -257,24 +298,14 @@ rv_status rv_dec_backward(rv_stage* s, rv_slot& slot, const void* grad_out, void
     }
     // attention half
     wgrad(2, a, d, dx1_16, d, d, d, gl + p.wo);                                                      // dWo = a^T dx1
+    RV_TRY(side_launch(1));   // (the side stream already waits for the LayerNorm backward above)
     RV_TRY(gemm(sh, st, dx1_16, d, 0, w + p.wo, d, 0, T, d, d, RV_EPI_BF16, dtmp, d));                   // da = dx1 Wo^T
     // (the attention backward also leaves partial column sums of dqkv: the qkv bias gradient)
     float* part_qkv = (float*)(s->work + p.w_part_qkv[par]);
     RV_TRY(rv_attn_bwd(qkv, a, dtmp, (const float*)(sb + p.s_lse), Dbuf, dqkv, p.mb, p.S, d, p.H, st, part_qkv));
     wgrad(3, u, d, dqkv, 3 * d, d, 3 * d, gl + p.wqkv);                                              // dWqkv = u^T dqkv
     RV_TRY(side_begin());
-    if (s->prof_on) {   // measurement aid: bracket the launch with events on its own stream
-      hipEvent_t e0 = nullptr, e1 = nullptr;
-      RV_HIP_TRY(hipEventCreate(&e0));
-      s->prof_ev.push_back(e0);
-      RV_HIP_TRY(hipEventCreate(&e1));
-      s->prof_ev.push_back(e1);
-      RV_HIP_TRY(hipEventRecord(e0, ws));
-      RV_TRY(rv_gemm_wgrad_grouped(wg, 4, ws));
-      RV_HIP_TRY(hipEventRecord(e1, ws));
-    } else {
-      RV_TRY(rv_gemm_wgrad_grouped(wg, 4, ws));
-    }
+    RV_TRY(side_launch(2));
     {
       float* out = gl + p.bqkv;
       RV_TRY(rv_reduce_rows(part_qkv, rv_attn_colsum_parts(p.mb, p.S), 3 * d, 3 * d, out, ws, upd(&out, 1)));
