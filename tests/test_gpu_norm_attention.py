@@ -13,7 +13,10 @@ from util import bf16_normal, close, host64, dev
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("T,d", [(64, 128), (100, 1024), (37, 1600), (16, 2048), (8, 4096), (5, 64)])
+# the last three rows: 8192 rows and more take the four-rows-per-wave forward (seven and four column
+# groups), 1792 is the widest row of the two-register-set forward
+@pytest.mark.parametrize("T,d", [(64, 128), (100, 1024), (37, 1600), (16, 2048), (8, 4096), (5, 64),
+                                 (8203, 1600), (8197, 1024), (23, 1792)])
 def test_layernorm_forward_backward(T, d):
     from paper_2401_01728_amd import kernels as k
     eps = 1e-5
